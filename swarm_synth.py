@@ -1,0 +1,139 @@
+"""Seeded synthetic inputs for the SWARM pipeline-stage workloads.
+
+This module is the only code shared by the CPU oracle's tests and the HIP
+path's tests / benchmark.  It holds none of the method's arithmetic: it only
+names the workload shapes and draws tensors from a seeded generator.
+
+Shapes follow the paper's layer descriptions (Section 4.2 and the appendix
+"Additional Details for Section 4.1": the "xxlarge" layer is d_model 4096,
+d_FFN 16384, 32 heads, sequence 512, microbatch 4; the large-scale run trains
+on sequences of up to 2048 tokens).  The paper's own throughput runs feed
+random samples, so no dataset is needed.
+
+Distributions (per workload): x_in ~ N(0,1); weight matrices and all biases
+~ N(0, 0.02); LayerNorm gains 1 + N(0, 0.02); grad_out ~ N(0, sigma_g).
+Every tensor has its own seed derived from (workload seed, tensor name), so
+generation order does not matter.  For bf16 workloads every tensor is rounded
+to bf16 (round-to-nearest-even) on the host; the returned fp32 arrays then
+hold exactly representable bf16 values, so both sides start from the same bits.
+"""
+from __future__ import annotations
+
+import dataclasses
+import zlib
+
+import numpy as np
+import torch
+
+BASE_SEED = 20230127
+
+PARAM_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str            # "f32" | "bf16"
+    d_model: int
+    n_heads: int
+    d_ffn: int
+    seq: int
+    batch: int
+    n_layers: int         # L distinct parameter sets
+    n_repeat: int         # R applications of each set in a row
+    grad_sigma: float
+    codec_block: int = 64
+    ln_eps: float = 1e-5
+    seed: int = BASE_SEED
+    boundary_codec: bool = False   # stage entry/exit tensors travel as int8
+
+    @property
+    def tokens(self) -> int:
+        return self.batch * self.seq
+
+    @property
+    def d_head(self) -> int:
+        return self.d_model // self.n_heads
+
+    def param_shapes(self) -> dict:
+        d, f = self.d_model, self.d_ffn
+        return {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (3 * d, d), "b_qkv": (3 * d,),
+                "w_o": (d, d), "b_o": (d,), "ln2_g": (d,), "ln2_b": (d,),
+                "w_1": (f, d), "b_1": (f,), "w_2": (d, f), "b_2": (d,)}
+
+    def replace(self, **kw) -> "Workload":
+        return dataclasses.replace(self, **kw)
+
+
+def _wl(i, name, **kw):
+    return Workload(name=name, seed=BASE_SEED + i, **kw)
+
+
+# The five configurations the benchmark description names.
+WORKLOADS = {
+    "block_f32_d256": _wl(1, "block_f32_d256", dtype="f32", d_model=256, n_heads=4, d_ffn=1024,
+                          seq=128, batch=4, n_layers=1, n_repeat=1, grad_sigma=1.0),
+    "stage2_bf16_d1024": _wl(2, "stage2_bf16_d1024", dtype="bf16", d_model=1024, n_heads=16, d_ffn=4096,
+                             seq=512, batch=8, n_layers=2, n_repeat=1, grad_sigma=1e-2),
+    "width_bf16_d1024": _wl(3, "width_bf16_d1024", dtype="bf16", d_model=1024, n_heads=8, d_ffn=4096,
+                            seq=512, batch=8, n_layers=1, n_repeat=1, grad_sigma=1e-2),
+    "width_bf16_d2048": _wl(3, "width_bf16_d2048", dtype="bf16", d_model=2048, n_heads=16, d_ffn=8192,
+                            seq=512, batch=8, n_layers=1, n_repeat=1, grad_sigma=1e-2),
+    "width_bf16_d4096": _wl(3, "width_bf16_d4096", dtype="bf16", d_model=4096, n_heads=32, d_ffn=16384,
+                            seq=512, batch=8, n_layers=1, n_repeat=1, grad_sigma=1e-2),
+    "shared4_bf16_d4096": _wl(4, "shared4_bf16_d4096", dtype="bf16", d_model=4096, n_heads=32, d_ffn=16384,
+                              seq=512, batch=4, n_layers=1, n_repeat=4, grad_sigma=1e-2),
+    "e2e_bf16_d4096": _wl(5, "e2e_bf16_d4096", dtype="bf16", d_model=4096, n_heads=32, d_ffn=16384,
+                          seq=2048, batch=4, n_layers=2, n_repeat=1, grad_sigma=1e-2,
+                          boundary_codec=True),
+}
+
+
+def _tensor_seed(seed: int, name: str) -> int:
+    return (seed * 1000003 + zlib.crc32(name.encode())) % (2 ** 63 - 1)
+
+
+def normal(seed: int, name: str, shape, mean: float = 0.0, std: float = 1.0,
+           bf16: bool = False) -> np.ndarray:
+    """fp32 array of N(mean, std) draws; with bf16=True the values are rounded to bf16."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(_tensor_seed(seed, name))
+    t = torch.randn(tuple(shape), generator=g, dtype=torch.float32)
+    if std != 1.0:
+        t.mul_(std)
+    if mean != 0.0:
+        t.add_(mean)
+    if bf16:
+        t = t.to(torch.bfloat16).to(torch.float32)
+    return t.numpy()
+
+
+def make_params(wl: Workload) -> list:
+    """List of L dicts (one per distinct block) of fp32 arrays."""
+    bf = wl.dtype == "bf16"
+    out = []
+    for l in range(wl.n_layers):
+        p = {}
+        for k, shp in wl.param_shapes().items():
+            if k in ("ln1_g", "ln2_g"):
+                p[k] = normal(wl.seed, f"L{l}.{k}", shp, 1.0, 0.02, bf)
+            else:
+                p[k] = normal(wl.seed, f"L{l}.{k}", shp, 0.0, 0.02, bf)
+        out.append(p)
+    return out
+
+
+def make_x_in(wl: Workload) -> np.ndarray:
+    return normal(wl.seed, "x_in", (wl.batch, wl.seq, wl.d_model), 0.0, 1.0, wl.dtype == "bf16")
+
+
+def make_grad_out(wl: Workload) -> np.ndarray:
+    return normal(wl.seed, "grad_out", (wl.batch, wl.seq, wl.d_model), 0.0, wl.grad_sigma,
+                  wl.dtype == "bf16")
+
+
+def codec_tensor(seed: int, n_elems: int, std: float = 1.0, bf16: bool = False,
+                 name: str = "codec") -> np.ndarray:
+    """Flat tensor with the value distribution of a boundary activation."""
+    return normal(seed, name, (n_elems,), 0.0, std, bf16)
