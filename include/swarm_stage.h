@@ -1,0 +1,126 @@
+/*
+ * swarm_stage.h - C ABI of the MI355X (gfx950) pipeline-stage library.
+ *
+ * The library does what ONE peer of ONE SWARM pipeline stage does to ONE
+ * microbatch (paper Section 3.2 "SWARM parallelism"; Section 2.1 "Pipeline
+ * parallelism"): forward through the stage's Transformer blocks, backward
+ * with recomputation of the forward (activation checkpointing, Section 3.2)
+ * and accumulation of parameter gradients, and the 8-bit blockwise codec of
+ * the tensors that cross stage boundaries (appendix "Compression-Aware
+ * Architectures", paragraph "Quantized activations").
+ *
+ * General rules for every call:
+ *   - every tensor pointer is a DEVICE pointer owned by the caller; the config
+ *     and the parameter/gradient structs are HOST structs that are read during
+ *     the call and never retained;
+ *   - the library allocates nothing, keeps no state between calls and never
+ *     frees or keeps a pointer; scratch memory comes in as `workspace`;
+ *   - work is enqueued on `hip_stream` (a hipStream_t cast to void*, NULL = the
+ *     default stream) and the call returns without synchronising;
+ *   - errors that the host can see (null pointer, unsupported shape, small
+ *     workspace) return a negative status BEFORE anything is launched and leave
+ *     all outputs untouched; a failed launch returns SWARM_ERR_LAUNCH;
+ *   - results are bitwise reproducible from call to call (no float atomics).
+ *   - all matrices are row-major with the last index contiguous.
+ */
+#ifndef SWARM_STAGE_H
+#define SWARM_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SWARM_OK = 0,
+  SWARM_ERR_NULL = -1,       /* a required pointer is NULL                    */
+  SWARM_ERR_SHAPE = -2,      /* a size or combination of sizes is unsupported */
+  SWARM_ERR_DTYPE = -3,      /* unknown dtype                                 */
+  SWARM_ERR_WORKSPACE = -4,  /* workspace smaller than *_workspace_bytes()    */
+  SWARM_ERR_LAUNCH = -5      /* the HIP runtime refused a launch              */
+} swarm_status;
+
+typedef enum { SWARM_F32 = 0, SWARM_BF16 = 1 } swarm_dtype;
+
+/* Shape of a stage.  Constraints: d_model % n_heads == 0; d_model / n_heads is 64
+ * or 128; d_model % 64 == 0; d_ffn % 64 == 0; all counts >= 1; seq >= 1.
+ * The stage applies parameter set 0 n_repeat times, then set 1 n_repeat times,
+ * ... (layer sharing, Sections 2.3 and 4.3: n_layers = 1, n_repeat = R). */
+typedef struct {
+  int32_t d_model, n_heads, d_ffn;
+  int32_t n_layers;          /* L distinct parameter sets in params[]              */
+  int32_t n_repeat;          /* R consecutive applications of each parameter set   */
+  int32_t batch, seq;        /* microbatch B, sequence length S                    */
+  int32_t dtype;             /* swarm_dtype of x, grads w.r.t. x and parameters    */
+  float   ln_eps;            /* LayerNorm epsilon, inside the square root          */
+} swarm_stage_config;
+
+/* One pre-LayerNorm Transformer block (the layer of the appendix "Additional
+ * Details for Section 4.1": d_model, d_FFN, heads).  For a token row x:
+ *   a = LN(x; ln1_g, ln1_b);  q|k|v = a w_qkv^T + b_qkv;
+ *   o = per-head causal softmax(q k^T / sqrt(d_head)) v;  h = x + o w_o^T + b_o;
+ *   c = LN(h; ln2_g, ln2_b);  y = h + gelu(c w_1^T + b_1) w_2^T + b_2   (erf GeLU).
+ * Weights are [out, in]; rows 0..d-1 of w_qkv produce q, d..2d-1 k, 2d..3d-1 v;
+ * head h owns columns h*d_head .. (h+1)*d_head-1 of q, k, v and o.
+ * Element type = config.dtype. */
+typedef struct {
+  const void *ln1_g, *ln1_b;   /* [d]           */
+  const void *w_qkv, *b_qkv;   /* [3d, d], [3d] */
+  const void *w_o,   *b_o;     /* [d, d],  [d]  */
+  const void *ln2_g, *ln2_b;   /* [d]           */
+  const void *w_1,   *b_1;     /* [f, d],  [f]  */
+  const void *w_2,   *b_2;     /* [d, f],  [d]  */
+} swarm_block_params;
+
+/* Gradients of one parameter set: same shapes, always fp32, ACCUMULATED into. */
+typedef struct {
+  float *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_1, *b_1, *w_2, *b_2;
+} swarm_block_grads;
+
+/* Bytes of device workspace the forward (for_backward = 0) or backward
+ * (for_backward != 0) call needs for this config; 0 if the config is invalid.
+ * The workspace must be 256-byte aligned. */
+size_t swarm_stage_workspace_bytes(const swarm_stage_config *cfg, int for_backward);
+
+/* Stage forward (Section 3.2: a peer applies its layers to the inputs received
+ * from the previous stage).  x_in [B,S,d] -> x_out [B,S,d], both of cfg->dtype;
+ * params[L] host array.  x_out is overwritten and must not alias x_in. */
+swarm_status swarm_stage_forward(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                 const void *x_in, void *x_out,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Stage backward (Section 3.2: a peer receives the gradient w.r.t. its outputs,
+ * computes the gradient w.r.t. its inputs and accumulates the gradients of its
+ * parameters; with activation checkpointing only x_in was kept, so the forward
+ * is recomputed here).  grad_out [B,S,d] -> grad_in [B,S,d] (overwritten, must
+ * not alias grad_out or x_in); grad_params[L] host array of fp32 device buffers
+ * that are ADDED to (the caller zeroes them at the start of a global batch);
+ * a shared parameter set receives the sum over its n_repeat applications. */
+swarm_status swarm_stage_backward(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                  const void *x_in, const void *grad_out, void *grad_in,
+                                  const swarm_block_grads *grad_params,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Codec encode ("Quantized activations": dynamic 8-bit quantisation with
+ * blockwise scaling).  tensor: n_elems values of `dtype`, flattened.  Per block of
+ * `block` consecutive elements (the last may be short), in IEEE fp32:
+ *   scale = max|x| / 127;  code = scale == 0 ? 0 : clamp(rint(x / scale), -127, 127)
+ * with rint = round-half-to-even.  codes [n_elems] int8, scales [ceil(n/block)] fp32.
+ * block must be 64.  n_elems == 0 is a no-op that returns SWARM_OK. */
+swarm_status swarm_codec_encode(const void *tensor, int32_t dtype, size_t n_elems, int32_t block,
+                                int8_t *codes, float *scales, void *hip_stream);
+
+/* Codec decode: tensor[i] = (float)codes[i] * scales[i / block], rounded to
+ * `dtype` (bf16: nearest-even).  Same constraints as encode. */
+swarm_status swarm_codec_decode(const int8_t *codes, const float *scales, size_t n_elems, int32_t block,
+                                void *tensor, int32_t dtype, void *hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char *swarm_status_string(swarm_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWARM_STAGE_H */

@@ -1,0 +1,12 @@
+"""MI355X-native pipeline-stage library for SWARM parallelism: Python binding.
+
+The compute lives in libswarm_stage.so (hand-written HIP for gfx950, C ABI in
+include/swarm_stage.h).  This package only marshals arguments; PyTorch supplies
+device memory and streams.  There is no CPU fallback: a missing library raises.
+"""
+from .binding import (  # noqa: F401
+    SWARM_F32, SWARM_BF16, SwarmError, StageConfig, lib_path, load_library,
+    swarm_stage_workspace_bytes, swarm_stage_forward, swarm_stage_backward,
+    swarm_codec_encode, swarm_codec_decode, swarm_status_string,
+    PARAM_FIELDS, EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,169 @@
+"""ctypes binding of the C ABI in include/swarm_stage.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+SWARM_F32, SWARM_BF16 = 0, 1
+PARAM_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+                "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
+EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm_stage_backward",
+                    "swarm_codec_encode", "swarm_codec_decode", "swarm_status_string")
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+
+
+class SwarmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, swarm_status_string(status), status))
+
+
+class _Config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
+                ("n_layers", C.c_int32), ("n_repeat", C.c_int32), ("batch", C.c_int32),
+                ("seq", C.c_int32), ("dtype", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class _BlockPtrs(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in PARAM_FIELDS]
+
+
+class StageConfig:
+    """Host-side description of a stage (mirrors swarm_stage_config)."""
+
+    def __init__(self, d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps=1e-5):
+        if isinstance(dtype, str):
+            dtype = {"f32": SWARM_F32, "bf16": SWARM_BF16}[dtype]
+        elif isinstance(dtype, torch.dtype):
+            dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
+        self.c = _Config(d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.c.dtype == SWARM_F32 else torch.bfloat16
+
+
+def lib_path() -> str:
+    return os.environ.get("SWARM_STAGE_LIB", os.path.join(_PKG, "libswarm_stage.so"))
+
+
+_lib = None
+
+
+def load_library():
+    """Load libswarm_stage.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            "%s not found: build it with `python -m paper_2301_11913_amd.build` "
+            "(the library has no CPU fallback)" % path)
+    lib = C.CDLL(path)
+    lib.swarm_stage_workspace_bytes.restype = C.c_size_t
+    lib.swarm_stage_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int]
+    lib.swarm_stage_forward.restype = C.c_int
+    lib.swarm_stage_forward.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs), C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_stage_backward.restype = C.c_int
+    lib.swarm_stage_backward.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs), C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.POINTER(_BlockPtrs), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_codec_encode.restype = C.c_int
+    lib.swarm_codec_encode.argtypes = [C.c_void_p, C.c_int32, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_void_p]
+    lib.swarm_codec_decode.restype = C.c_int
+    lib.swarm_codec_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_int32,
+                                       C.c_void_p]
+    lib.swarm_status_string.restype = C.c_char_p
+    lib.swarm_status_string.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def swarm_status_string(status: int) -> str:
+    return load_library().swarm_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to the stage library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SWARM_F32
+    if t.dtype == torch.bfloat16:
+        return SWARM_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _block_array(blocks: Sequence[Dict[str, torch.Tensor]]):
+    arr = (_BlockPtrs * len(blocks))()
+    for i, b in enumerate(blocks):
+        for k in PARAM_FIELDS:
+            setattr(arr[i], k, _ptr(b[k]))
+    return arr
+
+
+def swarm_stage_workspace_bytes(cfg: StageConfig, for_backward: bool) -> int:
+    return int(load_library().swarm_stage_workspace_bytes(C.byref(cfg.c), 1 if for_backward else 0))
+
+
+def swarm_stage_forward(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_in: torch.Tensor,
+                        x_out: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    st = load_library().swarm_stage_forward(C.byref(cfg.c), _block_array(params), _ptr(x_in), _ptr(x_out),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_stage_forward")
+
+
+def swarm_stage_backward(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_in: torch.Tensor,
+                         grad_out: torch.Tensor, grad_in: torch.Tensor,
+                         grad_params: List[Dict[str, torch.Tensor]], workspace: torch.Tensor,
+                         stream=None) -> None:
+    for g in grad_params:
+        for k in PARAM_FIELDS:
+            if g[k].dtype != torch.float32:
+                raise TypeError("grad_params must be fp32")
+    st = load_library().swarm_stage_backward(C.byref(cfg.c), _block_array(params), _ptr(x_in), _ptr(grad_out),
+                                             _ptr(grad_in), _block_array(grad_params), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_stage_backward")
+
+
+def swarm_codec_encode(tensor: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, block: int = 64,
+                       stream=None) -> None:
+    if codes.dtype != torch.int8 or scales.dtype != torch.float32:
+        raise TypeError("codes must be int8 and scales fp32")
+    st = load_library().swarm_codec_encode(_ptr(tensor), _dtype_code(tensor), tensor.numel(), block, _ptr(codes),
+                                           _ptr(scales), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_codec_encode")
+
+
+def swarm_codec_decode(codes: torch.Tensor, scales: torch.Tensor, tensor: torch.Tensor, block: int = 64,
+                       stream=None) -> None:
+    if codes.dtype != torch.int8 or scales.dtype != torch.float32:
+        raise TypeError("codes must be int8 and scales fp32")
+    st = load_library().swarm_codec_decode(_ptr(codes), _ptr(scales), tensor.numel(), block, _ptr(tensor),
+                                           _dtype_code(tensor), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_codec_decode")

@@ -1,0 +1,102 @@
+"""GPU parity of the codec kernels against the oracle: bit-exact codes, scales and decoded bits."""
+import numpy as np
+import pytest
+import torch
+
+import swarm_synth as synth
+from oracle import codec as ocodec
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(x, bf16):
+    t = torch.from_numpy(x)
+    return (t.to(torch.bfloat16) if bf16 else t).cuda()
+
+
+def _encode_gpu(x, bf16):
+    import paper_2301_11913_amd as sw
+    t = _dev(x, bf16)
+    n = t.numel()
+    codes = torch.full((n,), 77, dtype=torch.int8, device="cuda")
+    scales = torch.full(((n + 63) // 64,), -1.0, dtype=torch.float32, device="cuda")
+    sw.swarm_codec_encode(t, codes, scales)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.cpu().numpy()
+
+
+def _decode_gpu(codes, scales, n, bf16):
+    import paper_2301_11913_amd as sw
+    out = torch.full((n,), 3.0, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    sw.swarm_codec_decode(torch.from_numpy(codes).cuda(), torch.from_numpy(scales).cuda(), out)
+    torch.cuda.synchronize()
+    if bf16:
+        return out.view(torch.int16).cpu().numpy().view(np.uint16)
+    return out.cpu().numpy()
+
+
+# several 512-element wavefront tiles, a ragged tail, tiny, one block, and a boundary-tensor size
+SIZES = [1, 7, 63, 64, 65, 512, 64 * 1000 + 37, 4 * 128 * 256, 8 * 512 * 1024 + 8]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("std", [1.0, 1e-2])
+def test_codec_bit_exact(bf16, n, std):
+    x = synth.codec_tensor(31 + n, n, std=std, bf16=bf16)
+    if n > 200:
+        x[64:128] = 0.0                     # an all-zero block
+        x[130] = 127.0; x[131:136] = [0.5, 1.5, -2.5, 3.5, 126.5]   # exact ties under scale 1
+    rc, rs = ocodec.encode(x)
+    gc, gs = _encode_gpu(x, bf16)
+    assert np.array_equal(rs.view(np.uint32), gs.view(np.uint32))
+    assert np.array_equal(rc, gc)
+    ry = ocodec.decode(rc, rs, out="bf16" if bf16 else "f32")
+    gy = _decode_gpu(rc, rs, n, bf16)
+    if bf16:
+        assert np.array_equal(ry, gy)
+    else:
+        assert np.array_equal(ry.view(np.uint32), gy.view(np.uint32))
+
+
+def test_codec_all_bf16_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = ocodec.bf16_bits_to_f32(bits)
+    vals = vals[np.isfinite(vals)]
+    rng = np.random.default_rng(5)
+    x = np.concatenate([vals, rng.permutation(vals), rng.permutation(vals)[: 64 * 300]])
+    x = x[: (x.size // 64) * 64]
+    # keep per-block dynamic range moderate in the second half so codes are not all 0/127
+    rc, rs = ocodec.encode(x)
+    gc, gs = _encode_gpu(x, True)
+    assert np.array_equal(rs.view(np.uint32), gs.view(np.uint32))
+    assert np.array_equal(rc, gc)
+    srt = np.sort(vals)
+    srt = srt[: (srt.size // 64) * 64]       # sorted: neighbours share a block, all code values occur
+    rc, rs = ocodec.encode(srt)
+    gc, gs = _encode_gpu(srt, True)
+    assert np.array_equal(rs.view(np.uint32), gs.view(np.uint32)) and np.array_equal(rc, gc)
+    assert np.array_equal(ocodec.decode(rc, rs, out="bf16"), _decode_gpu(rc, rs, srt.size, True))
+
+
+def test_codec_empty_and_errors():
+    import paper_2301_11913_amd as sw
+    e = torch.empty(0, dtype=torch.bfloat16, device="cuda")
+    sw.swarm_codec_encode(e, torch.empty(0, dtype=torch.int8, device="cuda"),
+                          torch.empty(0, dtype=torch.float32, device="cuda"))
+    t = torch.zeros(128, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(128, dtype=torch.int8, device="cuda")
+    s = torch.zeros(2, dtype=torch.float32, device="cuda")
+    with pytest.raises(sw.SwarmError):
+        sw.swarm_codec_encode(t, c, s, block=32)
+
+
+def test_codec_full_boundary_tensor():
+    """The largest boundary tensor (4 x 2048 x 4096, bf16) in the benchmark's launch configuration."""
+    n = 4 * 2048 * 4096
+    x = synth.codec_tensor(77, n, std=1.0, bf16=True)
+    rc, rs = ocodec.encode(x)
+    gc, gs = _encode_gpu(x, True)
+    assert np.array_equal(rs.view(np.uint32), gs.view(np.uint32))
+    assert np.array_equal(rc, gc)
+    assert np.array_equal(ocodec.decode(rc, rs, out="bf16"), _decode_gpu(rc, rs, n, True))
