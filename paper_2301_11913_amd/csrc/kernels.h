@@ -1,0 +1,64 @@
+// Internal launch interface between the stage driver and the kernel files.
+// Everything here works on device pointers and enqueues on the given stream.
+#pragma once
+#include "common.h"
+
+namespace swarm {
+
+// ------------------------------------------------------------------ GEMM
+// C[M,N] (+)= sum_k A(m,k) * B(n,k) with fp32 accumulation.
+//   a_trans = false: A stored [M,K] (k contiguous, row pitch lda); true: stored [K,M].
+//   b_trans = false: B stored [N,K] (k contiguous, row pitch ldb); true: stored [K,N].
+// The three uses: forward  y = x W^T      (A = x [T,in],   B = W [out,in]:            F,F)
+//                 dgrad    dx = dy W      (A = dy [T,out], B = W [out,in] as [K,N]:    F,T)
+//                 wgrad    dW += dy^T x   (A = dy [T,out] as [K,M], B = x [T,in]:      T,T)
+enum GemmEpilogue {
+  EPI_STORE = 0,       // C = acc                                   (C in the activation dtype)
+  EPI_BIAS = 1,        // C = acc + bias[n]
+  EPI_BIAS_RESID = 2,  // C = acc + bias[n] + aux[m,n]
+  EPI_BIAS_GELU = 3,   // u = acc + bias[n]; C = gelu(u); C2 = u when C2 != nullptr
+  EPI_DGELU = 4,       // C = acc * gelu'(aux[m,n])
+  EPI_ACCUM_F32 = 5    // C (fp32) += acc
+};
+
+struct GemmArgs {
+  int M, N, K;
+  const void* A; int lda; bool a_trans;
+  const void* B; int ldb; bool b_trans;
+  void* C; int ldc;
+  int epilogue;
+  const void* bias;        // [N], activation dtype
+  const void* aux; int ldaux;   // [M,N] residual or pre-activation, activation dtype
+  void* C2; int ldc2;      // optional second output (pre-activation u)
+};
+
+// T = float: plain FMA tiles (parity configuration); T = bf16: MFMA kernel.
+swarm_status gemm_f32(const GemmArgs& g, hipStream_t st);
+swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st);
+// Generic (slow, any dtype) kernel used by the fp32 path; `bf16` selects the element type.
+swarm_status gemm_generic(const GemmArgs& g, bool bf16, hipStream_t st);
+
+// ------------------------------------------------------------------ LayerNorm / reductions
+// y = (x - mean) * rstd * gamma + beta over the last dim d; mean, rstd [T] fp32 are written.
+swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
+                           int T, int d, float eps, bool bf16, hipStream_t st);
+// dx = dres + LN-backward(dy), dgamma += sum_t dy*xhat, dbeta += sum_t dy.
+// `partial` is scratch of layernorm_bwd_scratch_floats(T, d) floats.
+size_t layernorm_bwd_scratch_floats(int T, int d);
+swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
+                           const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
+                           bool bf16, hipStream_t st);
+// out[n] += sum_t X[t,n]  (X [T,N] in the activation dtype, out fp32); scratch of colsum_scratch_floats floats.
+size_t colsum_scratch_floats(int T, int N);
+swarm_status colsum_accum(const void* X, int T, int N, float* out, float* partial, bool bf16, hipStream_t st);
+
+// ------------------------------------------------------------------ attention
+// qkv [T,3d] (q | k | v along the last dim; head h = columns h*dh..), causal, scores scaled by 1/sqrt(dh).
+// o [T,d]; lse [B,H,S] fp32 = log-sum-exp of the scaled scores of each query row.
+swarm_status attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int H, int dh, bool bf16,
+                           hipStream_t st);
+// dqkv [T,3d] from do [T,d]; delta [B,H,S] fp32 scratch.
+swarm_status attention_bwd(const void* qkv, const void* o, const void* dout, const float* lse, float* delta,
+                           void* dqkv, int B, int S, int H, int dh, bool bf16, hipStream_t st);
+
+}  // namespace swarm

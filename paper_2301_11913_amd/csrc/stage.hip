@@ -1,4 +1,294 @@
-#include "common.h"
-extern "C" size_t swarm_stage_workspace_bytes(const swarm_stage_config*, int) { return 0; }
-extern "C" swarm_status swarm_stage_forward(const swarm_stage_config*, const swarm_block_params*, const void*, void*, void*, size_t, void*) { return SWARM_ERR_SHAPE; }
-extern "C" swarm_status swarm_stage_backward(const swarm_stage_config*, const swarm_block_params*, const void*, const void*, void*, const swarm_block_grads*, void*, size_t, void*) { return SWARM_ERR_SHAPE; }
+// Stage driver: the fixed sequence of kernel launches for one pipeline stage's forward and
+// checkpoint-recomputing backward (paper Section 3.2), plus workspace carving and argument
+// validation.  Host code only; all arithmetic happens in the kernels it launches.
+#include <cstdlib>
+#include <vector>
+
+#include "kernels.h"
+
+namespace swarm {
+
+swarm_status attention_fwd_naive(const void*, void*, float*, int, int, int, int, bool, hipStream_t);
+swarm_status attention_bwd_naive(const void*, const void*, const void*, const float*, float*, void*, int, int, int,
+                                 int, bool, hipStream_t);
+
+namespace {
+
+struct Dims {
+  int T, d, f, H, dh, B, S, apps;
+  bool bf16;
+  size_t es;  // element size of the activation dtype
+};
+
+bool valid_config(const swarm_stage_config* c) {
+  if (!c) return false;
+  if (c->dtype != SWARM_F32 && c->dtype != SWARM_BF16) return false;
+  if (c->d_model < 64 || c->d_model % 64 || c->d_ffn < 64 || c->d_ffn % 64) return false;
+  if (c->d_model > 8192) return false;
+  if (c->n_heads < 1 || c->d_model % c->n_heads) return false;
+  const int dh = c->d_model / c->n_heads;
+  if (dh != 64 && dh != 128) return false;
+  if (c->n_layers < 1 || c->n_repeat < 1 || c->batch < 1 || c->seq < 1) return false;
+  if ((long long)c->batch * c->seq > (1ll << 24)) return false;
+  if (c->seq > 7000 && c->dtype == SWARM_F32) return false;   // direct attention keeps a score row in LDS
+  if (!(c->ln_eps > 0.0f)) return false;
+  return true;
+}
+
+Dims dims_of(const swarm_stage_config* c) {
+  Dims D;
+  D.B = c->batch; D.S = c->seq; D.T = c->batch * c->seq; D.d = c->d_model; D.f = c->d_ffn; D.H = c->n_heads;
+  D.dh = D.d / D.H; D.apps = c->n_layers * c->n_repeat; D.bf16 = c->dtype == SWARM_BF16;
+  D.es = D.bf16 ? 2 : 4;
+  return D;
+}
+
+// Bump allocator over the caller's workspace; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base((char*)b) {}
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+  size_t total() const { return (off + 255) & ~(size_t)255; }
+};
+
+// Intermediates of one block application.
+struct Saved {
+  const void* x;   // block input [T,d]
+  void *a, *qkv, *o, *h, *c, *u, *g;
+  float *mean1, *rstd1, *mean2, *rstd2, *lse;
+};
+
+void carve_saved(Carver& cv, const Dims& D, Saved& s, bool want_u) {
+  const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
+  s.a = cv.take(Td); s.qkv = cv.take(3 * Td); s.o = cv.take(Td); s.h = cv.take(Td); s.c = cv.take(Td);
+  s.u = want_u ? cv.take(Tf) : nullptr;
+  s.g = cv.take(Tf);
+  s.mean1 = (float*)cv.take((size_t)D.T * 4); s.rstd1 = (float*)cv.take((size_t)D.T * 4);
+  s.mean2 = (float*)cv.take((size_t)D.T * 4); s.rstd2 = (float*)cv.take((size_t)D.T * 4);
+  s.lse = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
+}
+
+swarm_status gemm(const Dims& D, const GemmArgs& g, hipStream_t st) {
+  return D.bf16 ? gemm_bf16(g, st) : gemm_f32(g, st);
+}
+
+#define SWARM_TRY(expr)                 \
+  do {                                  \
+    swarm_status _s = (expr);           \
+    if (_s != SWARM_OK) return _s;      \
+  } while (0)
+
+// y = block(x): writes every intermediate into `s`; the last GEMM is skipped when y == nullptr.
+swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Saved& s, void* y, float eps,
+                           hipStream_t st) {
+  const int T = D.T, d = D.d, f = D.f;
+  SWARM_TRY(layernorm_fwd(s.x, p.ln1_g, p.ln1_b, s.a, s.mean1, s.rstd1, T, d, eps, D.bf16, st));
+  GemmArgs q{};
+  q.M = T; q.N = 3 * d; q.K = d; q.A = s.a; q.lda = d; q.B = p.w_qkv; q.ldb = d; q.C = s.qkv; q.ldc = 3 * d;
+  q.epilogue = EPI_BIAS; q.bias = p.b_qkv;
+  SWARM_TRY(gemm(D, q, st));
+  SWARM_TRY(attention_fwd(s.qkv, s.o, s.lse, D.B, D.S, D.H, D.dh, D.bf16, st));
+  GemmArgs o{};
+  o.M = T; o.N = d; o.K = d; o.A = s.o; o.lda = d; o.B = p.w_o; o.ldb = d; o.C = s.h; o.ldc = d;
+  o.epilogue = EPI_BIAS_RESID; o.bias = p.b_o; o.aux = s.x; o.ldaux = d;
+  SWARM_TRY(gemm(D, o, st));
+  SWARM_TRY(layernorm_fwd(s.h, p.ln2_g, p.ln2_b, s.c, s.mean2, s.rstd2, T, d, eps, D.bf16, st));
+  GemmArgs f1{};
+  f1.M = T; f1.N = f; f1.K = d; f1.A = s.c; f1.lda = d; f1.B = p.w_1; f1.ldb = d; f1.C = s.g; f1.ldc = f;
+  f1.epilogue = EPI_BIAS_GELU; f1.bias = p.b_1; f1.C2 = s.u; f1.ldc2 = f;
+  SWARM_TRY(gemm(D, f1, st));
+  if (y) {
+    GemmArgs f2{};
+    f2.M = T; f2.N = d; f2.K = f; f2.A = s.g; f2.lda = f; f2.B = p.w_2; f2.ldb = f; f2.C = y; f2.ldc = d;
+    f2.epilogue = EPI_BIAS_RESID; f2.bias = p.b_2; f2.aux = s.h; f2.ldaux = d;
+    SWARM_TRY(gemm(D, f2, st));
+  }
+  return SWARM_OK;
+}
+
+struct BwdTemps {
+  void *du, *dc, *dh, *dout, *dqkv, *da;
+  float *delta, *partial;
+};
+
+// dW[out,in] += dY^T X  and  db[out] += colsum(dY)
+swarm_status weight_grads(const Dims& D, const void* dY, int n_out, const void* X, int n_in, float* dW, float* db,
+                          float* partial, hipStream_t st) {
+  SWARM_TRY(colsum_accum(dY, D.T, n_out, db, partial, D.bf16, st));
+  GemmArgs w{};
+  w.M = n_out; w.N = n_in; w.K = D.T; w.A = dY; w.lda = n_out; w.a_trans = true; w.B = X; w.ldb = n_in;
+  w.b_trans = true; w.C = dW; w.ldc = n_in; w.epilogue = EPI_ACCUM_F32;
+  return gemm(D, w, st);
+}
+
+// dX[T,in] = dY[T,out] W[out,in]
+swarm_status data_grad(const Dims& D, const void* dY, int n_out, const void* W, int n_in, void* dX, int epilogue,
+                       const void* aux, hipStream_t st) {
+  GemmArgs g{};
+  g.M = D.T; g.N = n_in; g.K = n_out; g.A = dY; g.lda = n_out; g.B = W; g.ldb = n_in; g.b_trans = true;
+  g.C = dX; g.ldc = n_in; g.epilogue = epilogue; g.aux = aux; g.ldaux = n_in;
+  return gemm(D, g, st);
+}
+
+swarm_status block_backward(const Dims& D, const swarm_block_params& p, const swarm_block_grads& gp, const Saved& s,
+                            const BwdTemps& t, const void* dy, void* dx, hipStream_t st) {
+  const int d = D.d, f = D.f;
+  // y = h + gelu(u) W2^T + b2
+  SWARM_TRY(weight_grads(D, dy, d, s.g, f, gp.w_2, gp.b_2, t.partial, st));
+  SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.du, EPI_DGELU, s.u, st));
+  // u = c W1^T + b1
+  SWARM_TRY(weight_grads(D, t.du, f, s.c, d, gp.w_1, gp.b_1, t.partial, st));
+  SWARM_TRY(data_grad(D, t.du, f, p.w_1, d, t.dc, EPI_STORE, nullptr, st));
+  // c = LN2(h);  dh = dy + LN2'(dc)
+  SWARM_TRY(layernorm_bwd(t.dc, s.h, s.mean2, s.rstd2, p.ln2_g, dy, t.dh, gp.ln2_g, gp.ln2_b, t.partial, D.T, d,
+                          D.bf16, st));
+  // h = x + o Wo^T + bo
+  SWARM_TRY(weight_grads(D, t.dh, d, s.o, d, gp.w_o, gp.b_o, t.partial, st));
+  SWARM_TRY(data_grad(D, t.dh, d, p.w_o, d, t.dout, EPI_STORE, nullptr, st));
+  SWARM_TRY(attention_bwd(s.qkv, s.o, t.dout, s.lse, t.delta, t.dqkv, D.B, D.S, D.H, D.dh, D.bf16, st));
+  // qkv = a Wqkv^T + bqkv
+  SWARM_TRY(weight_grads(D, t.dqkv, 3 * d, s.a, d, gp.w_qkv, gp.b_qkv, t.partial, st));
+  SWARM_TRY(data_grad(D, t.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
+  // a = LN1(x);  dx = dh + LN1'(da)
+  SWARM_TRY(layernorm_bwd(t.da, s.x, s.mean1, s.rstd1, p.ln1_g, t.dh, dx, gp.ln1_g, gp.ln1_b, t.partial, D.T, d,
+                          D.bf16, st));
+  return SWARM_OK;
+}
+
+struct FwdPlan {
+  Saved s;
+  void* z[2];
+};
+
+size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
+  Carver cv(ws);
+  const size_t Td = (size_t)D.T * D.d * D.es;
+  P.s = Saved{};
+  carve_saved(cv, D, P.s, false);
+  P.z[0] = D.apps > 1 ? cv.take(Td) : nullptr;
+  P.z[1] = D.apps > 1 ? cv.take(Td) : nullptr;
+  return cv.total();
+}
+
+struct BwdPlan {
+  std::vector<Saved> saved;
+  std::vector<void*> xbuf;   // inputs of applications 1..apps-1
+  BwdTemps t;
+  void* dz[2];
+};
+
+size_t plan_backward(const Dims& D, void* ws, BwdPlan& P) {
+  Carver cv(ws);
+  const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
+  P.saved.assign(D.apps, Saved{});
+  P.xbuf.assign(D.apps, nullptr);
+  for (int i = 0; i < D.apps; ++i) {
+    carve_saved(cv, D, P.saved[i], true);
+    if (i > 0) P.xbuf[i] = cv.take(Td);
+  }
+  P.t.du = cv.take(Tf); P.t.dc = cv.take(Td); P.t.dh = cv.take(Td); P.t.dout = cv.take(Td);
+  P.t.dqkv = cv.take(3 * Td); P.t.da = cv.take(Td);
+  P.t.delta = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
+  size_t pf = layernorm_bwd_scratch_floats(D.T, D.d);
+  pf = std::max(pf, colsum_scratch_floats(D.T, std::max(3 * D.d, D.f)));
+  P.t.partial = (float*)cv.take(pf * 4);
+  P.dz[0] = D.apps > 1 ? cv.take(Td) : nullptr;
+  P.dz[1] = D.apps > 1 ? cv.take(Td) : nullptr;
+  return cv.total();
+}
+
+bool params_ok(const swarm_block_params* p, int L) {
+  for (int l = 0; l < L; ++l) {
+    const void* const* f = (const void* const*)&p[l];
+    for (int i = 0; i < 12; ++i)
+      if (!f[i]) return false;
+  }
+  return true;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+}  // namespace swarm
+
+using namespace swarm;
+
+extern "C" size_t swarm_stage_workspace_bytes(const swarm_stage_config* cfg, int for_backward) {
+  if (!valid_config(cfg)) return 0;
+  const Dims D = dims_of(cfg);
+  if (for_backward) {
+    BwdPlan P;
+    return plan_backward(D, nullptr, P);
+  }
+  FwdPlan P;
+  return plan_forward(D, nullptr, P);
+}
+
+extern "C" swarm_status swarm_stage_forward(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                            const void* x_in, void* x_out, void* workspace, size_t workspace_bytes,
+                                            void* hip_stream) {
+  if (!cfg || !params || !x_in || !x_out || !workspace) return SWARM_ERR_NULL;
+  if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
+  if (!params_ok(params, cfg->n_layers)) return SWARM_ERR_NULL;
+  if (x_in == x_out || !aligned16(x_in) || !aligned16(x_out) || ((uintptr_t)workspace & 255)) return SWARM_ERR_SHAPE;
+  const Dims D = dims_of(cfg);
+  FwdPlan P;
+  if (plan_forward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const void* cur = x_in;
+  int app = 0;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
+      void* y = (app == D.apps - 1) ? x_out : P.z[app & 1];
+      P.s.x = cur;
+      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st));
+      cur = y;
+    }
+  return SWARM_OK;
+}
+
+extern "C" swarm_status swarm_stage_backward(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                             const void* x_in, const void* grad_out, void* grad_in,
+                                             const swarm_block_grads* grad_params, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream) {
+  if (!cfg || !params || !x_in || !grad_out || !grad_in || !grad_params || !workspace) return SWARM_ERR_NULL;
+  if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
+  if (!params_ok(params, cfg->n_layers) || !params_ok((const swarm_block_params*)grad_params, cfg->n_layers))
+    return SWARM_ERR_NULL;
+  if (grad_in == grad_out || grad_in == x_in || !aligned16(x_in) || !aligned16(grad_out) || !aligned16(grad_in) ||
+      ((uintptr_t)workspace & 255))
+    return SWARM_ERR_SHAPE;
+  const Dims D = dims_of(cfg);
+  BwdPlan P;
+  if (plan_backward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  // recompute the forward from the stage input, keeping every application's intermediates
+  const void* cur = x_in;
+  int app = 0;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
+      P.saved[app].x = cur;
+      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];   // the stage output itself is not needed
+      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
+      cur = y;
+    }
+  // reverse sweep
+  const void* dy = grad_out;
+  app = D.apps - 1;
+  for (int l = cfg->n_layers - 1; l >= 0; --l)
+    for (int r = cfg->n_repeat - 1; r >= 0; --r, --app) {
+      void* dx = (app == 0) ? grad_in : P.dz[app & 1];
+      SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, dx, st));
+      dy = dx;
+    }
+  return SWARM_OK;
+}

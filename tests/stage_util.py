@@ -1,0 +1,71 @@
+"""Helpers for the GPU parity tests: run a workload through the C ABI and through the oracle."""
+import numpy as np
+import torch
+
+import swarm_synth as synth
+from oracle import stage as osg
+
+
+def to_dev(arr, wl):
+    t = torch.from_numpy(np.ascontiguousarray(arr))
+    if wl.dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.cuda()
+
+
+def run_gpu(wl, params, x, G, n_backward_calls=1, forward=True, backward=True):
+    """Returns dict(x_out, grad_in, grads[list of dict]) as float64 numpy arrays."""
+    import paper_2301_11913_amd as sw
+    cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
+                         wl.ln_eps)
+    dp = [{k: to_dev(p[k], wl) for k in sw.PARAM_FIELDS} for p in params]
+    xd, Gd = to_dev(x, wl), to_dev(G, wl)
+    out = {}
+    if forward:
+        ws = torch.empty(sw.swarm_stage_workspace_bytes(cfg, False), dtype=torch.uint8, device="cuda")
+        y = torch.full_like(xd, 7.0)
+        sw.swarm_stage_forward(cfg, dp, xd, y, ws)
+        torch.cuda.synchronize()
+        out["x_out"] = y.float().cpu().numpy().astype(np.float64)
+        del ws
+    if backward:
+        ws = torch.empty(sw.swarm_stage_workspace_bytes(cfg, True), dtype=torch.uint8, device="cuda")
+        gin = torch.full_like(xd, 7.0)
+        gp = [{k: torch.zeros(p[k].shape, dtype=torch.float32, device="cuda") for k in sw.PARAM_FIELDS}
+              for p in params]
+        for _ in range(n_backward_calls):
+            sw.swarm_stage_backward(cfg, dp, xd, Gd, gin, gp, ws)
+        torch.cuda.synchronize()
+        out["grad_in"] = gin.float().cpu().numpy().astype(np.float64)
+        out["grads"] = [{k: g[k].cpu().numpy().astype(np.float64) for k in sw.PARAM_FIELDS} for g in gp]
+    return out
+
+
+def run_oracle(wl, params, x, G, dt=np.float64, forward=True, backward=True):
+    out = {}
+    if forward:
+        out["x_out"] = osg.stage_forward(params, x, wl.n_heads, wl.n_repeat, wl.ln_eps, dt)
+    if backward:
+        grads = osg.zero_grads(params, dt)
+        out["grad_in"] = osg.stage_backward(params, x, G, grads, wl.n_heads, wl.n_repeat, wl.ln_eps, dt)
+        out["grads"] = grads
+    return out
+
+
+def max_norm_err(a, b):
+    """max|a-b| / max|b| (the parity metric of the benchmark description)."""
+    den = float(np.max(np.abs(b)))
+    return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - b))) / (den if den > 0 else 1.0)
+
+
+def compare(gpu, ref, tol):
+    errs = {}
+    for k in ("x_out", "grad_in"):
+        if k in gpu:
+            errs[k] = max_norm_err(gpu[k], ref[k])
+    if "grads" in gpu:
+        for l, (g, r) in enumerate(zip(gpu["grads"], ref["grads"])):
+            for k in g:
+                errs["L%d.%s" % (l, k)] = max_norm_err(g[k], r[k])
+    bad = {k: v for k, v in errs.items() if not (v <= tol)}
+    return errs, bad

@@ -1,0 +1,89 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the header
+declares, and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2301_11913_amd as sw
+from paper_2301_11913_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "swarm_stage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(swarm_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sw.lib_path()):
+        pytest.skip("libswarm_stage.so not built")
+    return sw.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    syms = _header_symbols()
+    assert set(syms) == set(sw.EXPORTED_SYMBOLS)
+    for s in syms:
+        assert getattr(lib, s) is not None
+
+
+def test_status_strings(lib):
+    assert sw.swarm_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert sw.swarm_status_string(code) not in ("ok", "unknown status")
+    assert sw.swarm_status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes_and_config_validation(lib):
+    ok = sw.StageConfig(256, 4, 1024, 1, 1, 4, 128, "f32")
+    fwd = sw.swarm_stage_workspace_bytes(ok, False)
+    bwd = sw.swarm_stage_workspace_bytes(ok, True)
+    T, d, f = 512, 256, 1024
+    assert fwd >= (7 * T * d + T * f) * 4 and fwd % 256 == 0
+    assert bwd > fwd
+    # more applications need more backward workspace, forward only the ping-pong buffers
+    ok4 = sw.StageConfig(256, 4, 1024, 1, 4, 4, 128, "f32")
+    assert sw.swarm_stage_workspace_bytes(ok4, True) > 2.5 * bwd
+    for bad in (sw.StageConfig(250, 5, 1024, 1, 1, 4, 128, "f32"),      # d_model % 64
+                sw.StageConfig(256, 8, 1024, 1, 1, 4, 128, "f32"),      # d_head 32
+                sw.StageConfig(256, 4, 1000, 1, 1, 4, 128, "f32"),      # d_ffn % 64
+                sw.StageConfig(256, 4, 1024, 0, 1, 4, 128, "f32"),
+                sw.StageConfig(256, 4, 1024, 1, 1, 4, 0, "f32"),
+                sw.StageConfig(256, 4, 1024, 1, 1, 4, 128, "f32", ln_eps=0.0)):
+        assert sw.swarm_stage_workspace_bytes(bad, False) == 0
+        assert sw.swarm_stage_workspace_bytes(bad, True) == 0
+
+
+def test_null_and_shape_errors_without_gpu(lib):
+    cfg = sw.StageConfig(256, 4, 1024, 1, 1, 4, 128, "f32")
+    blocks = (binding._BlockPtrs * 1)()
+    # null tensors
+    assert lib.swarm_stage_forward(C.byref(cfg.c), blocks, None, None, None, 0, None) == -1
+    assert lib.swarm_stage_backward(C.byref(cfg.c), blocks, None, None, None, blocks, None, 0, None) == -1
+    # non-null tensors but null parameter pointers
+    assert lib.swarm_stage_forward(C.byref(cfg.c), blocks, 4096, 8192, 256 * 40, 1 << 30, None) == -1
+    bad = sw.StageConfig(256, 4, 1024, 1, 1, 4, 128, "f32")
+    bad.c.dtype = 9
+    assert lib.swarm_stage_forward(C.byref(bad.c), blocks, 4096, 8192, 256 * 40, 1 << 30, None) == -3
+    # codec: wrong block, wrong dtype, null, misaligned; empty is fine
+    assert lib.swarm_codec_encode(4096, 1, 128, 32, 8192, 12288, None) == -2
+    assert lib.swarm_codec_encode(4096, 7, 128, 64, 8192, 12288, None) == -3
+    assert lib.swarm_codec_encode(None, 1, 128, 64, 8192, 12288, None) == -1
+    assert lib.swarm_codec_encode(4098, 1, 128, 64, 8192, 12288, None) == -2
+    assert lib.swarm_codec_encode(None, 1, 0, 64, None, None, None) == 0
+    assert lib.swarm_codec_decode(None, None, 0, 64, None, 1, None) == 0
+    assert lib.swarm_codec_decode(None, 4096, 64, 64, 8192, 1, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setenv("SWARM_STAGE_LIB", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()
+    monkeypatch.delenv("SWARM_STAGE_LIB")
+    monkeypatch.setattr(binding, "_lib", None)
