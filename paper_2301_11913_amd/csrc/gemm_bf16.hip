@@ -1,4 +1,293 @@
+// bf16 MFMA GEMM for gfx950 with fp32 accumulation:  C[M,N] (+)= sum_k A(m,k) B(n,k).
+//
+// Workgroup tile BM x BN x 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) sub-tile made
+// of 32x32 accumulators fed by v_mfma_f32_32x32x16_bf16.  Both operand tiles live in LDS as
+// [rows][64 k] bf16 (128-byte rows) with the 16-byte chunks of a row XOR-swizzled so that the
+// 64-lane 16-byte fragment reads are bank-conflict free; LDS is double buffered and the next
+// K-slice is prefetched into registers while the current one is multiplied (one barrier per slice).
+//
+// Operands whose contraction index is the slow (row) index in memory - W in the data-gradient
+// GEMM, both operands in the weight-gradient GEMM - are transposed on their way into LDS: a lane
+// loads an 8(k) x 4 patch with 8-byte loads and permutes it in registers into four 16-byte LDS
+// rows.  Nothing is transposed through HBM.
+//
+// Launch order maps consecutive workgroups to the 8 XCDs round-robin, so tile ids are remapped
+// to give every XCD a contiguous band of tiles (its own L2 then sees the reuse), and tiles are
+// walked in groups of rows to keep the B panel resident.
+//
+// Deterministic: one workgroup owns an output tile and walks K in order.
 #include "kernels.h"
+#include "gelu.h"
+
 namespace swarm {
-swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) { return gemm_generic(g, true, st); }
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BK = 64;
+
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// element offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 tile
+__device__ __forceinline__ int tile_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
+
+struct KArgs {
+  const bf16_raw* A; const bf16_raw* B;
+  int M, N, K, lda, ldb;
+  void* C; int ldc;
+  int epilogue;
+  const bf16_raw* bias; const bf16_raw* aux; int ldaux;
+  bf16_raw* C2; int ldc2;
+  int tiles_m, tiles_n;
+};
+
+// Global -> registers for one operand tile (BR rows of the GEMM x 64 k).
+template <int BR, int NT, bool TRANS, bool GUARD>
+struct TileLoader {
+  // non-transposed: BR*8 16-byte chunks; transposed: (BR/4)*8 patches of 8(k) x 4
+  static constexpr int NI = TRANS ? ((BR / 4) * 8 + NT - 1) / NT : (BR * 8) / NT;
+  static constexpr int REGS = TRANS ? NI * 8 : NI * 2;   // in uint2 units
+  uint2 r[REGS];
+
+  __device__ __forceinline__ void load(const bf16_raw* __restrict__ p, int ld, int rows, int kdim, int r0, int k0,
+                                       int tid) {
+    if constexpr (!TRANS) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int it = tid + i * NT;
+        const int row = it >> 3, chunk = it & 7;
+        const int gr = r0 + row, gk = k0 + chunk * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (!GUARD || (gr < rows && gk < kdim)) v = *reinterpret_cast<const uint4*>(p + (size_t)gr * ld + gk);
+        r[2 * i] = make_uint2(v.x, v.y);
+        r[2 * i + 1] = make_uint2(v.z, v.w);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int it = tid + i * NT;
+        const int xc = it % (BR / 4), kg = it / (BR / 4);
+        const int col = r0 + xc * 4;
+        const bool in = (NI * NT == (BR / 4) * 8) || kg < 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int gk = k0 + kg * 8 + j;
+          uint2 v = make_uint2(0, 0);
+          if (in && (!GUARD || (gk < kdim && col < rows)))
+            v = *reinterpret_cast<const uint2*>(p + (size_t)gk * ld + col);
+          r[i * 8 + j] = v;
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(bf16_raw* __restrict__ lds, int tid) const {
+    if constexpr (!TRANS) {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int it = tid + i * NT;
+        const int row = it >> 3, chunk = it & 7;
+        *reinterpret_cast<uint4*>(lds + tile_off(row, chunk)) =
+            make_uint4(r[2 * i].x, r[2 * i].y, r[2 * i + 1].x, r[2 * i + 1].y);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int it = tid + i * NT;
+        const int xc = it % (BR / 4), kg = it / (BR / 4);
+        if ((NI * NT != (BR / 4) * 8) && kg >= 8) continue;
+        const uint2* q = r + i * 8;
+        // q[j] = 4 consecutive columns of k-row j; build, per column x, the 8 k values
+        uint4 o0, o1, o2, o3;
+        o0.x = __builtin_amdgcn_perm(q[1].x, q[0].x, 0x05040100u); o1.x = __builtin_amdgcn_perm(q[1].x, q[0].x, 0x07060302u);
+        o0.y = __builtin_amdgcn_perm(q[3].x, q[2].x, 0x05040100u); o1.y = __builtin_amdgcn_perm(q[3].x, q[2].x, 0x07060302u);
+        o0.z = __builtin_amdgcn_perm(q[5].x, q[4].x, 0x05040100u); o1.z = __builtin_amdgcn_perm(q[5].x, q[4].x, 0x07060302u);
+        o0.w = __builtin_amdgcn_perm(q[7].x, q[6].x, 0x05040100u); o1.w = __builtin_amdgcn_perm(q[7].x, q[6].x, 0x07060302u);
+        o2.x = __builtin_amdgcn_perm(q[1].y, q[0].y, 0x05040100u); o3.x = __builtin_amdgcn_perm(q[1].y, q[0].y, 0x07060302u);
+        o2.y = __builtin_amdgcn_perm(q[3].y, q[2].y, 0x05040100u); o3.y = __builtin_amdgcn_perm(q[3].y, q[2].y, 0x07060302u);
+        o2.z = __builtin_amdgcn_perm(q[5].y, q[4].y, 0x05040100u); o3.z = __builtin_amdgcn_perm(q[5].y, q[4].y, 0x07060302u);
+        o2.w = __builtin_amdgcn_perm(q[7].y, q[6].y, 0x05040100u); o3.w = __builtin_amdgcn_perm(q[7].y, q[6].y, 0x07060302u);
+        const int row = xc * 4;
+        *reinterpret_cast<uint4*>(lds + tile_off(row + 0, kg)) = o0;
+        *reinterpret_cast<uint4*>(lds + tile_off(row + 1, kg)) = o1;
+        *reinterpret_cast<uint4*>(lds + tile_off(row + 2, kg)) = o2;
+        *reinterpret_cast<uint4*>(lds + tile_off(row + 3, kg)) = o3;
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool GUARD>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(KArgs p) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int STAGE = (BM + BN) * BK;   // elements per LDS stage
+  extern __shared__ __attribute__((aligned(16))) bf16_raw lds[];
+
+  // ---- tile id -> (tile_m, tile_n): XCD-contiguous bands, then row groups of 8
+  int pid = blockIdx.x;
+  const int ntiles = p.tiles_m * p.tiles_n;
+  if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+  constexpr int GM = 8;
+  const int per_group = GM * p.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GM;
+  const int gsz = min(p.tiles_m - first_m, GM);
+  const int tile_m = first_m + (pid % per_group) % gsz;
+  const int tile_n = (pid % per_group) / gsz;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, lg = lane >> 5;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  TileLoader<BM, NT, A_T, GUARD> la;
+  TileLoader<BN, NT, B_T, GUARD> lb;
+
+  const int KT = (p.K + BK - 1) / BK;
+  la.load(p.A, p.lda, p.M, p.K, m0, 0, tid);
+  lb.load(p.B, p.ldb, p.N, p.K, n0, 0, tid);
+  la.store(lds, tid);
+  lb.store(lds + BM * BK, tid);
+  __syncthreads();
+
+  // per-lane fragment offsets: row (l32) fixes the swizzle, chunk = 2*kk + lg
+  int foff[4];
+  {
+    const int s = swz(l32);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) foff[kk] = l32 * BK + (((2 * kk + lg) ^ s) << 3);
+  }
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const bf16_raw* sA = lds + (kt & 1) * STAGE;
+    const bf16_raw* sB = sA + BM * BK;
+    const bool more = kt + 1 < KT;
+    if (more) {
+      la.load(p.A, p.lda, p.M, p.K, m0, (kt + 1) * BK, tid);
+      lb.load(p.B, p.ldb, p.N, p.K, n0, (kt + 1) * BK, tid);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 a[FM], b[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+        a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sA + (wm * WTM + i * 32) * BK + foff[kk]));
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sB + (wn * WTN + j * 32) * BK + foff[kk]));
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      bf16_raw* dA = lds + ((kt + 1) & 1) * STAGE;
+      la.store(dA, tid);
+      lb.store(dA + BM * BK, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue.  acc[i][j][r] is C(row, col) with
+  //   row = m0 + wm*WTM + i*32 + 8*(r/4) + 4*lg + (r%4),  col = n0 + wn*WTN + j*32 + l32
+  const int epi = p.epilogue;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int col = n0 + wn * WTN + j * 32 + l32;
+    if (GUARD && col >= p.N) continue;
+    float bias = 0.f;
+    if (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU) bias = bf16_bits_to_float(p.bias[col]);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+        if (GUARD && row >= p.M) continue;
+        const float v = acc[i][j][r];
+        const size_t ci = (size_t)row * p.ldc + col;
+        if (epi == EPI_ACCUM_F32) {
+          float* c = reinterpret_cast<float*>(p.C);
+          c[ci] += v;
+        } else {
+          bf16_raw* c = reinterpret_cast<bf16_raw*>(p.C);
+          float out;
+          if (epi == EPI_STORE) {
+            out = v;
+          } else if (epi == EPI_BIAS) {
+            out = v + bias;
+          } else if (epi == EPI_BIAS_RESID) {
+            out = v + bias + bf16_bits_to_float(p.aux[(size_t)row * p.ldaux + col]);
+          } else if (epi == EPI_BIAS_GELU) {
+            const float u = v + bias;
+            if (p.C2) p.C2[(size_t)row * p.ldc2 + col] = (bf16_raw)float_to_bf16_bits(u);
+            out = gelu_f(u);
+          } else {  // EPI_DGELU
+            out = v * gelu_grad_f(bf16_bits_to_float(p.aux[(size_t)row * p.ldaux + col]));
+          }
+          c[ci] = (bf16_raw)float_to_bf16_bits(out);
+        }
+      }
+    }
+  }
 }
+
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool GUARD>
+swarm_status launch(const KArgs& k, hipStream_t st) {
+  constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * BK * sizeof(bf16_raw);
+  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, A_T, B_T, GUARD>;
+  static bool attr_set = false;   // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
+        hipSuccess)
+      return SWARM_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n), dim3(WM * WN * 64), lds_bytes, st, k);
+  return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN, bool GUARD>
+swarm_status launch_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t st) {
+  if (!a_t && !b_t) return launch<BM, BN, WM, WN, false, false, GUARD>(k, st);
+  if (!a_t && b_t) return launch<BM, BN, WM, WN, false, true, GUARD>(k, st);
+  if (a_t && b_t) return launch<BM, BN, WM, WN, true, true, GUARD>(k, st);
+  return SWARM_ERR_SHAPE;
+}
+
+}  // namespace
+
+swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
+  // vector loads need 8-element alignment of every contiguous run
+  const bool vec_ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0) && (((uintptr_t)g.A & 15) == 0) &&
+                      (((uintptr_t)g.B & 15) == 0) && (g.a_trans ? g.M % 8 == 0 : g.K % 8 == 0) &&
+                      (g.b_trans ? g.N % 8 == 0 : g.K % 8 == 0);
+  if (!vec_ok || (g.a_trans && !g.b_trans)) return gemm_generic(g, true, st);
+  KArgs k;
+  k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
+  k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
+  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;
+  const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  if (big_tiles >= 160) {
+    k.tiles_m = (g.M + 255) / 256; k.tiles_n = (g.N + 255) / 256;
+    const bool guard = (g.M % 256) || (g.N % 256) || (g.K % BK);
+    return guard ? launch_layout<256, 256, 2, 4, true>(k, g.a_trans, g.b_trans, st)
+                 : launch_layout<256, 256, 2, 4, false>(k, g.a_trans, g.b_trans, st);
+  }
+  k.tiles_m = (g.M + 127) / 128; k.tiles_n = (g.N + 127) / 128;
+  const bool guard = (g.M % 128) || (g.N % 128) || (g.K % BK);
+  return guard ? launch_layout<128, 128, 2, 2, true>(k, g.a_trans, g.b_trans, st)
+               : launch_layout<128, 128, 2, 2, false>(k, g.a_trans, g.b_trans, st);
+}
+
+}  // namespace swarm

@@ -1,0 +1,27 @@
+// Kernel-level entry points for unit tests and micro-benchmarks of single kernels.
+// They are not part of the stage ABI (include/swarm_stage.h); arguments are device pointers.
+#include "kernels.h"
+
+using namespace swarm;
+
+// C[M,N] (+)= A(m,k) B(n,k); layouts and epilogues as in GemmArgs.  dtype: 0 fp32, 1 bf16.
+extern "C" int swarm_kernel_gemm(int dtype, int M, int N, int K, const void* A, int lda, int a_trans, const void* B,
+                                 int ldb, int b_trans, void* C, int ldc, int epilogue, const void* bias,
+                                 const void* aux, int ldaux, void* C2, int ldc2, void* stream) {
+  GemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.a_trans = a_trans != 0; g.B = B; g.ldb = ldb;
+  g.b_trans = b_trans != 0; g.C = C; g.ldc = ldc; g.epilogue = epilogue; g.bias = bias; g.aux = aux;
+  g.ldaux = ldaux; g.C2 = C2; g.ldc2 = ldc2;
+  return dtype ? gemm_bf16(g, (hipStream_t)stream) : gemm_f32(g, (hipStream_t)stream);
+}
+
+extern "C" int swarm_kernel_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H,
+                                          int dh, void* stream) {
+  return attention_fwd(qkv, o, lse, B, S, H, dh, dtype != 0, (hipStream_t)stream);
+}
+
+extern "C" int swarm_kernel_attention_bwd(int dtype, const void* qkv, const void* o, const void* dout,
+                                          const float* lse, float* delta, void* dqkv, int B, int S, int H, int dh,
+                                          void* stream) {
+  return attention_bwd(qkv, o, dout, lse, delta, dqkv, B, S, H, dh, dtype != 0, (hipStream_t)stream);
+}
