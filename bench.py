@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the SWARM pipeline-stage hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+One step = what a stage peer does for one microbatch: decode the int8 stage input and the int8
+output gradient, stage forward, checkpoint-recomputing stage backward (parameter gradients
+accumulated), encode the stage output and the input gradient.  Inputs are synthetic and already
+resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+
+
+def model_flops(wl):
+    """Paper convention (Table 6: 6 * parameters * tokens for fwd+bwd) plus the causal attention term."""
+    T, d, f, S, B = wl.tokens, wl.d_model, wl.d_ffn, wl.seq, wl.batch
+    gemm = 2.0 * T * (4 * d * d + 2 * d * f)
+    attn = 2.0 * B * wl.n_heads * wl.d_head * S * (S + 1)
+    return 3.0 * (gemm + attn) * wl.n_layers * wl.n_repeat
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, on the host cores, on a bounded sample of the workload:
+    one sequence (batch 1) through ONE block application, forward + backward, plus the codec on
+    that sequence's boundary tensors.  Scaled to the workload's block count."""
+    import numpy as np
+    import swarm_synth as synth
+    from oracle import stage as osg, codec as ocodec
+    seq = min(wl.seq, 2048)
+    sample = wl.replace(batch=1, seq=seq, n_layers=1, n_repeat=1)
+    params, x, G = synth.make_params(sample), synth.make_x_in(sample), synth.make_grad_out(sample)
+    t0 = time.perf_counter()
+    if wl.boundary_codec:
+        cx, sx = ocodec.encode(x.reshape(-1))
+        x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(x.shape)
+        cg, sg = ocodec.encode(G.reshape(-1))
+        G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(G.shape)
+    y = osg.stage_forward(params, x, sample.n_heads, 1, sample.ln_eps, np.float64)
+    grads = osg.zero_grads(params, np.float64)
+    gin = osg.stage_backward(params, x, G, grads, sample.n_heads, 1, sample.ln_eps, np.float64)
+    if wl.boundary_codec:
+        ocodec.encode(y.astype(np.float32).reshape(-1))
+        ocodec.encode(gin.astype(np.float32).reshape(-1))
+    dt = time.perf_counter() - t0
+    apps = wl.n_layers * wl.n_repeat
+    import torch
+    return {"value": seq / (dt * apps), "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": "fp64 numpy oracle, 1 sequence of %d tokens through 1 of %d block applications "
+                      "(fwd + recomputing bwd%s), %.1f s; rate divided by the block count"
+                      % (seq, apps, " + codec" if wl.boundary_codec else "", dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="e2e_bf16_d4096")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this library is the per-peer, single-GPU path of a SWARM stage; peers of a stage share "
+              "nothing but the gradient all-reduce, which is outside it. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import swarm_synth as synth
+    import paper_2301_11913_amd as sw
+
+    wl = synth.WORKLOADS[args.workload]
+    lib = sw.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+
+    def rn(shape, std, mean=0.0):
+        return (torch.randn(shape, generator=g, device=dev, dtype=torch.float32) * std + mean).to(dt)
+
+    params = []
+    for _ in range(wl.n_layers):
+        p = {k: rn(s, 0.02, 1.0 if k in ("ln1_g", "ln2_g") else 0.0) for k, s in wl.param_shapes().items()}
+        params.append(p)
+    grads = [{k: torch.zeros(s, dtype=torch.float32, device=dev) for k, s in wl.param_shapes().items()}
+             for _ in range(wl.n_layers)]
+    shape = (wl.batch, wl.seq, wl.d_model)
+    n = wl.tokens * wl.d_model
+    x_src, g_src = rn(shape, 1.0), rn(shape, wl.grad_sigma)
+    cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
+                         wl.ln_eps)
+    ws = torch.empty(max(sw.swarm_stage_workspace_bytes(cfg, True), sw.swarm_stage_workspace_bytes(cfg, False)),
+                     dtype=torch.uint8, device=dev)
+    x, G, y, gin = (torch.empty(shape, dtype=dt, device=dev) for _ in range(4))
+    codes = {k: torch.empty(n, dtype=torch.int8, device=dev) for k in ("x", "g", "y", "gin")}
+    scales = {k: torch.empty(n // 64, dtype=torch.float32, device=dev) for k in ("x", "g", "y", "gin")}
+    if wl.boundary_codec:
+        sw.swarm_codec_encode(x_src, codes["x"], scales["x"])
+        sw.swarm_codec_encode(g_src, codes["g"], scales["g"])
+    else:
+        x.copy_(x_src)
+        G.copy_(g_src)
+
+    def step():
+        if wl.boundary_codec:
+            sw.swarm_codec_decode(codes["x"], scales["x"], x)
+            sw.swarm_codec_decode(codes["g"], scales["g"], G)
+        sw.swarm_stage_forward(cfg, params, x, y, ws)
+        sw.swarm_stage_backward(cfg, params, x, G, gin, grads, ws)
+        if wl.boundary_codec:
+            sw.swarm_codec_encode(y, codes["y"], scales["y"])
+            sw.swarm_codec_encode(gin, codes["gin"], scales["gin"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # roofline of the dominant kernel (the bf16 MFMA GEMM): event pairs on the launch stream around
+    # every GEMM launch of the same K steps
+    roofline = None
+    if wl.dtype == "bf16":
+        lib.swarm_kernel_timing_enable.restype = C.c_int
+        lib.swarm_kernel_timing_collect.restype = C.c_int
+        lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        tot_ms, tot_fl, launches = 0.0, 0.0, 0
+        for _ in range(args.steps):
+            lib.swarm_kernel_timing_enable(1)
+            step()
+            ms, fl = C.c_double(), C.c_double()
+            nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
+            tot_ms += ms.value; tot_fl += fl.value; launches += nl
+        lib.swarm_kernel_timing_enable(0)
+        achieved = tot_fl / (tot_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": round(achieved, 1),
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": None, "launches_per_step": launches // args.steps,
+                    "avg_launch_us": round(tot_ms * 1e3 / launches, 1),
+                    "flops_per_launch": tot_fl / launches,
+                    "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+
+    tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
+    out = {"metric": "stage fwd+bwd tokens/s (+ int8 boundary codec)", "value": round(tokens_per_s, 1),
+           "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": wl.dtype, "data": "synthetic",
+           "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ffn": wl.d_ffn,
+                      "seq": wl.seq, "microbatch": wl.batch, "blocks": wl.n_layers, "repeat": wl.n_repeat,
+                      "codec": "int8 absmax block 64 on stage input/output and their gradients"
+                      if wl.boundary_codec else "none"},
+           "model_tflops_per_s": round(model_flops(wl) / (ms_per_step * 1e-3) / 1e12, 1),
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -16,6 +16,8 @@
 // walked in groups of rows to keep the B panel resident.
 //
 // Deterministic: one workgroup owns an output tile and walks K in order.
+#include <vector>
+
 #include "kernels.h"
 #include "gelu.h"
 
@@ -265,9 +267,31 @@ swarm_status launch_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t st) {
   return SWARM_ERR_SHAPE;
 }
 
+// Optional per-launch timing of the MFMA GEMM (off by default): an event pair on the launch stream
+// around every launch, read back by swarm_kernel_timing_collect().  Measurement plumbing only.
+struct GemmTimer {
+  static constexpr int kMax = 8192;
+  bool enabled = false;
+  int used = 0;
+  std::vector<hipEvent_t> ev;      // 2 per launch
+  std::vector<double> flops;
+} g_timer;
+
 }  // namespace
 
+swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st);
+
 swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
+  if (!g_timer.enabled || g_timer.used >= GemmTimer::kMax) return gemm_bf16_launch(g, st);
+  const int i = g_timer.used++;
+  g_timer.flops[i] = 2.0 * g.M * g.N * g.K;
+  (void)hipEventRecord(g_timer.ev[2 * i], st);
+  swarm_status s = gemm_bf16_launch(g, st);
+  (void)hipEventRecord(g_timer.ev[2 * i + 1], st);
+  return s;
+}
+
+swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   // vector loads need 8-element alignment of every contiguous run
   const bool vec_ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0) && (((uintptr_t)g.A & 15) == 0) &&
                       (((uintptr_t)g.B & 15) == 0) && (g.a_trans ? g.M % 8 == 0 : g.K % 8 == 0) &&
@@ -291,3 +315,35 @@ swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
 }
 
 }  // namespace swarm
+
+// Turn per-launch GEMM timing on (creates the event pool once) or off; resets the counters.
+extern "C" int swarm_kernel_timing_enable(int on) {
+  using namespace swarm;
+  if (on && g_timer.ev.empty()) {
+    g_timer.ev.resize(2 * GemmTimer::kMax);
+    g_timer.flops.resize(GemmTimer::kMax);
+    for (auto& e : g_timer.ev)
+      if (hipEventCreate(&e) != hipSuccess) return -1;
+  }
+  g_timer.enabled = on != 0;
+  g_timer.used = 0;
+  return 0;
+}
+
+// Synchronises, then returns the number of timed launches and their summed duration / flops.
+extern "C" int swarm_kernel_timing_collect(double* total_ms, double* total_flops) {
+  using namespace swarm;
+  double ms = 0, fl = 0;
+  for (int i = 0; i < g_timer.used; ++i) {
+    if (hipEventSynchronize(g_timer.ev[2 * i + 1]) != hipSuccess) return -1;
+    float t = 0;
+    if (hipEventElapsedTime(&t, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]) != hipSuccess) return -1;
+    ms += t;
+    fl += g_timer.flops[i];
+  }
+  *total_ms = ms;
+  *total_flops = fl;
+  const int n = g_timer.used;
+  g_timer.used = 0;
+  return n;
+}

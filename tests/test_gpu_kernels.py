@@ -92,3 +92,67 @@ def test_gemm_layouts(a_t, b_t, shape):
 def test_gemm_epilogues(epi, shape):
     M, N, K = shape
     gemm_case(M, N, K, False, epi == 4, epi, seed=epi)
+
+
+# ------------------------------------------------------------------ attention
+def _attn_lib():
+    lib = _lib()
+    lib.swarm_kernel_attention_fwd.restype = C.c_int
+    lib.swarm_kernel_attention_fwd.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p]
+    lib.swarm_kernel_attention_bwd.restype = C.c_int
+    lib.swarm_kernel_attention_bwd.argtypes = [C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4 + [C.c_void_p]
+    return lib
+
+
+def _attn_ref(qkv, dout, B, S, H, dh):
+    """fp64 definition: per (b,h) causal softmax(q k^T / sqrt(dh)) v and its gradient."""
+    d = H * dh
+    x = qkv.reshape(B, S, 3, H, dh).transpose(2, 0, 3, 1, 4)       # [3,B,H,S,dh]
+    q, k, v = x[0], x[1], x[2]
+    s = q @ k.transpose(0, 1, 3, 2) / math.sqrt(dh)
+    mask = np.tril(np.ones((S, S), dtype=bool))
+    s = np.where(mask, s, -np.inf)
+    mx = s.max(-1, keepdims=True)
+    e = np.exp(s - mx)
+    den = e.sum(-1, keepdims=True)
+    p = e / den
+    o = p @ v
+    lse = (mx + np.log(den))[..., 0]
+    do = dout.reshape(B, S, H, dh).transpose(0, 2, 1, 3)
+    dv = p.transpose(0, 1, 3, 2) @ do
+    dp = do @ v.transpose(0, 1, 3, 2)
+    ds = p * (dp - (p * dp).sum(-1, keepdims=True))
+    dq = ds @ k / math.sqrt(dh)
+    dk = ds.transpose(0, 1, 3, 2) @ q / math.sqrt(dh)
+    back = lambda t: t.transpose(0, 2, 1, 3).reshape(B, S, d)
+    return back(o), lse, np.concatenate([back(dq), back(dk), back(dv)], axis=-1)
+
+
+@pytest.mark.parametrize("shape", [(2, 128, 2, 64), (1, 512, 3, 128), (3, 37, 2, 128), (2, 200, 1, 64),
+                                   (1, 1, 2, 64), (1, 1000, 2, 128), (2, 2048, 2, 128)])
+def test_attention_bf16(shape):
+    B, S, H, dh = shape
+    lib = _attn_lib()
+    d = H * dh
+    qkv = _bf(synth.normal(S + dh, "qkv", (B, S, 3 * d), std=1.5))
+    dout = _bf(synth.normal(S + dh, "dout", (B, S, d)))
+    ro, rlse, rdqkv = _attn_ref(qkv.double().numpy(), dout.double().numpy(), B, S, H, dh)
+    qd, dod = qkv.cuda(), dout.cuda()
+    o = torch.full((B, S, d), 9.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((B, H, S), 9.0, dtype=torch.float32, device="cuda")
+    assert lib.swarm_kernel_attention_fwd(1, qd.data_ptr(), o.data_ptr(), lse.data_ptr(), B, S, H, dh, None) == 0
+    torch.cuda.synchronize()
+    eo = np.max(np.abs(o.double().cpu().numpy() - ro)) / np.max(np.abs(ro))
+    el = np.max(np.abs(lse.double().cpu().numpy() - rlse))
+    assert eo < 1e-2, eo
+    assert el < 2e-2, el
+    delta = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    dqkv = torch.full((B, S, 3 * d), 9.0, dtype=torch.bfloat16, device="cuda")
+    assert lib.swarm_kernel_attention_bwd(1, qd.data_ptr(), o.data_ptr(), dod.data_ptr(), lse.data_ptr(),
+                                          delta.data_ptr(), dqkv.data_ptr(), B, S, H, dh, None) == 0
+    torch.cuda.synchronize()
+    got = dqkv.double().cpu().numpy()
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        den = max(np.max(np.abs(rdqkv[..., sl])), 1e-3 * np.max(np.abs(rdqkv)))   # S = 1 has dq = dk = 0 exactly
+        e = np.max(np.abs(got[..., sl] - rdqkv[..., sl])) / den
+        assert e < 1.5e-2, (name, e)
