@@ -16,16 +16,13 @@
 // walked in groups of rows to keep the B panel resident.
 //
 // Deterministic: one workgroup owns an output tile and walks K in order.
+#include <cstdlib>
 #include <vector>
 
-#include "kernels.h"
-#include "gelu.h"
+#include "gemm_bf16_common.h"
 
 namespace swarm {
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int BK = 64;
 
@@ -33,15 +30,6 @@ __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1
 // element offset of 16-byte chunk `chunk` (0..7) of row `row` in a [rows][64] bf16 tile
 __device__ __forceinline__ int tile_off(int row, int chunk) { return row * BK + ((chunk ^ swz(row)) << 3); }
 
-struct KArgs {
-  const bf16_raw* A; const bf16_raw* B;
-  int M, N, K, lda, ldb;
-  void* C; int ldc;
-  int epilogue;
-  const bf16_raw* bias; const bf16_raw* aux; int ldaux;
-  bf16_raw* C2; int ldc2;
-  int tiles_m, tiles_n;
-};
 
 // Global -> registers for one operand tile (BR rows of the GEMM x 64 k).
 template <int BR, int NT, bool TRANS, bool GUARD>
@@ -127,17 +115,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(KArgs p) {
   constexpr int STAGE = (BM + BN) * BK;   // elements per LDS stage
   extern __shared__ __attribute__((aligned(16))) bf16_raw lds[];
 
-  // ---- tile id -> (tile_m, tile_n): XCD-contiguous bands, then row groups of 8
-  int pid = blockIdx.x;
-  const int ntiles = p.tiles_m * p.tiles_n;
-  if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
-  constexpr int GM = 8;
-  const int per_group = GM * p.tiles_n;
-  const int group = pid / per_group;
-  const int first_m = group * GM;
-  const int gsz = min(p.tiles_m - first_m, GM);
-  const int tile_m = first_m + (pid % per_group) % gsz;
-  const int tile_n = (pid % per_group) / gsz;
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x;
@@ -201,47 +180,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(KArgs p) {
     __syncthreads();
   }
 
-  // ---- epilogue.  acc[i][j][r] is C(row, col) with
-  //   row = m0 + wm*WTM + i*32 + 8*(r/4) + 4*lg + (r%4),  col = n0 + wn*WTN + j*32 + l32
-  const int epi = p.epilogue;
-#pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int col = n0 + wn * WTN + j * 32 + l32;
-    if (GUARD && col >= p.N) continue;
-    float bias = 0.f;
-    if (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU) bias = bf16_bits_to_float(p.bias[col]);
-#pragma unroll
-    for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-        if (GUARD && row >= p.M) continue;
-        const float v = acc[i][j][r];
-        const size_t ci = (size_t)row * p.ldc + col;
-        if (epi == EPI_ACCUM_F32) {
-          float* c = reinterpret_cast<float*>(p.C);
-          c[ci] += v;
-        } else {
-          bf16_raw* c = reinterpret_cast<bf16_raw*>(p.C);
-          float out;
-          if (epi == EPI_STORE) {
-            out = v;
-          } else if (epi == EPI_BIAS) {
-            out = v + bias;
-          } else if (epi == EPI_BIAS_RESID) {
-            out = v + bias + bf16_bits_to_float(p.aux[(size_t)row * p.ldaux + col]);
-          } else if (epi == EPI_BIAS_GELU) {
-            const float u = v + bias;
-            if (p.C2) p.C2[(size_t)row * p.ldc2 + col] = (bf16_raw)float_to_bf16_bits(u);
-            out = gelu_f(u);
-          } else {  // EPI_DGELU
-            out = v * gelu_grad_f(bf16_bits_to_float(p.aux[(size_t)row * p.ldaux + col]));
-          }
-          c[ci] = (bf16_raw)float_to_bf16_bits(out);
-        }
-      }
-    }
-  }
+  // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
+  gemm_epilogue<FM, FN, GUARD>(p, acc, m0 + wm * WTM, n0 + wn * WTN, l32, lg,
+                               reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool GUARD>
@@ -280,6 +221,7 @@ struct GemmTimer {
 }  // namespace
 
 swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st);
+swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st);
 
 swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
   if (!g_timer.enabled || g_timer.used >= GemmTimer::kMax) return gemm_bf16_launch(g, st);
@@ -293,10 +235,18 @@ swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
 
 swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   // vector loads need 8-element alignment of every contiguous run
-  const bool vec_ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0) && (((uintptr_t)g.A & 15) == 0) &&
-                      (((uintptr_t)g.B & 15) == 0) && (g.a_trans ? g.M % 8 == 0 : g.K % 8 == 0) &&
-                      (g.b_trans ? g.N % 8 == 0 : g.K % 8 == 0);
+  auto al16 = [](const void* q) { return ((uintptr_t)q & 15) == 0; };
+  bool vec_ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0) && al16(g.A) && al16(g.B) &&
+                (g.a_trans ? g.M % 8 == 0 : g.K % 8 == 0) && (g.b_trans ? g.N % 8 == 0 : g.K % 8 == 0);
+  if (g.epilogue != EPI_ACCUM_F32)   // the bf16 epilogue moves 8-element chunks
+    vec_ok = vec_ok && g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.bias || al16(g.bias)) &&
+             (!g.aux || (al16(g.aux) && g.ldaux % 8 == 0)) && (!g.C2 || (al16(g.C2) && g.ldc2 % 8 == 0));
   if (!vec_ok || (g.a_trans && !g.b_trans)) return gemm_generic(g, true, st);
+  static const bool use_dma = std::getenv("SWARM_GEMM_NO_DMA") == nullptr;
+  if (use_dma) {
+    const swarm_status s = gemm_bf16_dma(g, st);   // tile-aligned shapes: pipelined direct-to-LDS kernel
+    if (s != SWARM_ERR_SHAPE) return s;
+  }
   KArgs k;
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;

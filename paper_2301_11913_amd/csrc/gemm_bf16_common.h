@@ -1,0 +1,142 @@
+// Pieces shared by the bf16 MFMA GEMM kernels: argument block, tile order, fused epilogue.
+#pragma once
+#include "kernels.h"
+#include "gelu.h"
+
+namespace swarm {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+struct KArgs {
+  const bf16_raw* A; const bf16_raw* B;
+  int M, N, K, lda, ldb;
+  void* C; int ldc;
+  int epilogue;
+  const bf16_raw* bias; const bf16_raw* aux; int ldaux;
+  bf16_raw* C2; int ldc2;
+  int tiles_m, tiles_n;
+};
+
+// Launch order maps consecutive workgroups to the 8 XCDs round-robin; give every XCD a contiguous band
+// of tiles (its own L2 then sees the reuse) and walk tiles in groups of 8 rows to keep a B panel resident.
+__device__ __forceinline__ void tile_of_block(const KArgs& p, int& tile_m, int& tile_n) {
+  int pid = blockIdx.x;
+  const int ntiles = p.tiles_m * p.tiles_n;
+  if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+  constexpr int GM = 8;
+  const int per_group = GM * p.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GM;
+  const int gsz = min(p.tiles_m - first_m, GM);
+  tile_m = first_m + (pid % per_group) % gsz;
+  tile_n = (pid % per_group) / gsz;
+}
+
+// acc[i][j][r] is C(row, col) with row = row0 + i*32 + 8*(r/4) + 4*lg + (r%4), col = col0 + j*32 + l32
+// (row0/col0 = first row/column of this wavefront's sub-tile).
+//
+// bf16 outputs: an accumulator lane holds one column and scattered rows, which would mean 2-byte stores.
+// Each wavefront therefore turns its sub-tile 32 rows at a time through a private LDS patch
+// (`stage`, 32 x kEpiPitch floats) and writes rows out with 16-byte loads/stores: 8 lanes cover 128
+// contiguous bytes of a row, for C, for the residual / pre-activation input and for the second output.
+// fp32 accumulate (wgrad) already touches 128 contiguous bytes per row and stays direct.
+constexpr int kEpiPitch = 68;   // floats; 4-bank skew between consecutive rows keeps the row reads conflict free
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __uint_as_float(w[i] << 16);
+    x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+__device__ __forceinline__ uint4 pack8_bf16(const float (&x)[8]) {
+  return make_uint4(cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3]), cvt_pk_bf16(x[4], x[5]), cvt_pk_bf16(x[6], x[7]));
+}
+
+template <int FM, int FN, bool GUARD>
+__device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][FN], int row0, int col0, int l32,
+                                              int lg, float* stage) {
+  const int epi = p.epilogue;
+  if (epi == EPI_ACCUM_F32) {
+    float* c = reinterpret_cast<float*>(p.C);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int col = col0 + j * 32 + l32;
+      if (GUARD && col >= p.N) continue;
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row0 + i * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
+          if (GUARD && row >= p.M) continue;
+          c[(size_t)row * p.ldc + col] += acc[i][j][r];
+        }
+    }
+    return;
+  }
+  constexpr int COLS = 32 * FN;
+  constexpr int LPR = COLS / 8;          // lanes per row on the way out
+  constexpr int RPP = 64 / LPR;          // rows per pass
+  const int lane = l32 + 32 * lg;
+  const int c8 = lane % LPR, rsub = lane / LPR;
+  const int col = col0 + 8 * c8;
+  const bool col_ok = !GUARD || col < p.N;     // N is a multiple of 8, so a chunk is all in or all out
+  float bias[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) bias[e] = 0.f;
+  if (col_ok && (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU))
+    unpack8(*reinterpret_cast<const uint4*>(p.bias + col), bias);
+  bf16_raw* C = reinterpret_cast<bf16_raw*>(p.C);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+#pragma unroll
+    for (int ps = 0; ps < 32 / RPP; ++ps) {
+      const int rl = ps * RPP + rsub;
+      const int row = row0 + i * 32 + rl;
+      const float4 v0 = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 8 * c8);
+      const float4 v1 = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 8 * c8 + 4);
+      if (!col_ok || (GUARD && row >= p.M)) continue;
+      float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      if (epi == EPI_BIAS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] += bias[e];
+      } else if (epi == EPI_BIAS_RESID) {
+        float a[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = x[e] + bias[e] + a[e];
+      } else if (epi == EPI_BIAS_GELU) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] += bias[e];
+        if (p.C2) *reinterpret_cast<uint4*>(p.C2 + (size_t)row * p.ldc2 + col) = pack8_bf16(x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = gelu_f(x[e]);
+      } else if (epi == EPI_DGELU) {
+        float a[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_f(a[e]);
+      }
+      *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + col) = pack8_bf16(x);
+    }
+  }
+}
+
+}  // namespace
+}  // namespace swarm

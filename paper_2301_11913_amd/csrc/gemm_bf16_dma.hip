@@ -1,0 +1,228 @@
+// bf16 MFMA GEMM, pipelined variant for tile-aligned shapes:  C[M,N] (+)= sum_k A(m,k) B(n,k).
+//
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes per lane,
+// no staging registers) through a ring of NS stages of K-depth 32, so NS-1 slices are in flight: an
+// HBM miss takes longer than one slice of MFMA work, and every K slice is new to the L2.
+// A load instruction fills 1 KiB of contiguous LDS; which 16-byte global chunk a lane fetches is free,
+// which gives the bank-conflict-avoiding XOR swizzles below for nothing.
+//
+//   operand with k contiguous in memory  : LDS tile [rows][32 k] (64-byte rows), fragment = one
+//                                          ds_read_b128 per 32x16 operand block;
+//   operand with k as the slow index     : LDS tile [32 k][rows] exactly as in memory, fragment = two
+//   (W in dgrad, both operands in wgrad)   ds_read_b64_tr_b16 (the LDS transpose read hands lane n the
+//                                          four k-consecutive values of column n).
+//
+// One workgroup owns one output tile and walks K in order: deterministic.
+#include "gemm_bf16_common.h"
+
+namespace swarm {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+
+#ifndef EXP_DBK
+#define EXP_DBK 64
+#endif
+#ifndef EXP_NS
+#define EXP_NS 2
+#endif
+constexpr int DBK = EXP_DBK;   // K depth of a stage (32 or 64)
+constexpr int NS = EXP_NS;     // LDS stages
+constexpr int KCH = DBK / 8;   // 16-byte chunks per row of a non-transposed tile
+
+// chunk swizzle of a non-transposed tile: makes the 16 rows that one LDS pass reads (64 banks x 4 B)
+// hit 16 distinct 16-byte bank groups
+__device__ __forceinline__ int swz_rows(int row) {
+  return DBK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3);
+}
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Issue the loads of one operand tile (BR rows of the GEMM x 32 k) into LDS at `lds` (BR*32 elements).
+// NW wavefronts share the BR/16 load instructions round-robin.
+template <int BR, int NW, bool TRANS>
+__device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
+                                           int wave, int lane) {
+  constexpr int NINST = BR * DBK / 512;
+  static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
+#pragma unroll
+  for (int t = 0; t < NINST / NW; ++t) {
+    const int q = wave + t * NW;            // wave-uniform instruction index; fills lds + q*512 .. +512
+    const bf16_raw* src;
+    if constexpr (!TRANS) {
+      const int row = q * (64 / KCH) + lane / KCH;
+      const int chunk = (lane % KCH) ^ swz_rows(row);
+      src = g + (size_t)(r0 + row) * ld + k0 + chunk * 8;
+    } else {
+      constexpr int CPR = BR / 8;           // 16-byte chunks per k-row
+      const int krow = q * (64 / CPR) + lane / CPR;
+      const int chunk = (lane % CPR) ^ (2 * (krow & 3));
+      src = g + (size_t)(k0 + krow) * ld + r0 + chunk * 8;
+    }
+    __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds + q * 512), 16, 0, 0);
+  }
+}
+
+// Fragment (32 GEMM rows x 16 k) for v_mfma_f32_32x32x16_bf16 from a non-transposed tile.
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_raw* tile, int row_base, int kk, int l32, int lg) {
+  const int row = row_base + l32;
+  const int chunk = (2 * kk + lg) ^ swz_rows(l32);
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + row * DBK + chunk * 8));
+}
+
+// Same fragment from a [32 k][BR] tile through the LDS transpose read.
+template <int BR>
+__device__ __forceinline__ bf16x8 frag_trans(const bf16_raw* tile, int col_base, int kk, int lane) {
+  const int l16 = lane & 15, grp = lane >> 4;
+  const int lg = grp >> 1;
+  const int col = col_base + 16 * (grp & 1) + 4 * (l16 & 3);
+  const int kq = l16 >> 2;                                   // k-row inside the group of four
+  const int chunk = (col >> 3) ^ (2 * kq);
+  const int off = chunk * 8 + (col & 4);
+  const int krow = 16 * kk + 8 * lg + kq;
+  const bf16_raw* p0 = tile + krow * BR + off;
+  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p0);
+  const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0 + 4 * BR));
+  uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+  return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
+}
+
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
+  constexpr int NW = WM * WN;
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int FM = WTM / 32, FN = WTN / 32;
+  constexpr int STAGE = (BM + BN) * DBK;              // elements
+  constexpr int IPW = (BM + BN) * DBK / 512 / NW;       // load instructions per wavefront per stage
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int l32 = lane & 31, lg = lane >> 5;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int KT = p.K / DBK;
+  auto issue = [&](int kt) {
+    bf16_raw* st = lds + (kt % NS) * STAGE;
+    issue_tile<BM, NW, A_T>(p.A, p.lda, m0, kt * DBK, st, wave, lane);
+    issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, kt * DBK, st + BM * DBK, wave, lane);
+  };
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < KT) issue(s);
+  if (KT >= NS - 1) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const bool steady = kt + NS - 1 < KT;
+#ifndef EXP_NOLOAD
+    if (steady) issue(kt + NS - 1);     // refills the stage that was read in iteration kt-1
+#endif
+    const bf16_raw* sA = lds + (kt % NS) * STAGE;
+    const bf16_raw* sB = sA + BM * DBK;
+#ifndef EXP_LOADONLY
+#pragma unroll
+    for (int kk = 0; kk < DBK / 16; ++kk) {
+      bf16x8 a[FM], b[FN];
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        if constexpr (A_T) a[i] = frag_trans<BM>(sA, wm * WTM + i * 32, kk, lane);
+        else a[i] = frag_rows(sA, wm * WTM + i * 32, kk, l32, lg);
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        if constexpr (B_T) b[j] = frag_trans<BN>(sB, wn * WTN + j * 32, kk, lane);
+        else b[j] = frag_rows(sB, wn * WTN + j * 32, kk, l32, lg);
+      }
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#ifndef EXP_NOMFMA
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+#else
+          acc[i][j][0] += __builtin_bit_cast(float, __builtin_bit_cast(uint4, a[i]).x ^ __builtin_bit_cast(uint4, b[j]).y);
+#endif
+        }
+    }
+#endif
+    // slice kt+1 must have landed (this wavefront's part), then all wavefronts meet: everybody's part of
+    // slice kt+1 is visible and everybody is done reading slice kt
+#ifndef EXP_NOLOAD
+    if (steady) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
+#endif
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS reads of slice kt are complete
+#ifndef EXP_NOBARRIER
+    __builtin_amdgcn_s_barrier();
+#endif
+  }
+
+  // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
+  gemm_epilogue<FM, FN, false>(p, acc, m0 + wm * WTM, n0 + wn * WTN, l32, lg,
+                               reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
+}
+
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
+swarm_status launch_dma(const KArgs& k, hipStream_t st) {
+  constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * DBK * sizeof(bf16_raw);
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, A_T, B_T>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
+        hipSuccess)
+      return SWARM_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n), dim3(WM * WN * 64), lds_bytes, st, k);
+  return launch_status();
+}
+
+template <int BM, int BN, int WM, int WN>
+swarm_status launch_dma_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t st) {
+  if (!a_t && !b_t) return launch_dma<BM, BN, WM, WN, false, false>(k, st);
+  if (!a_t && b_t) return launch_dma<BM, BN, WM, WN, false, true>(k, st);
+  if (a_t && b_t) return launch_dma<BM, BN, WM, WN, true, true>(k, st);
+  return SWARM_ERR_SHAPE;
+}
+
+}  // namespace
+
+// Returns SWARM_ERR_SHAPE when the problem is not tile-aligned (the caller then uses the guarded kernel).
+swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
+  if (g.a_trans && !g.b_trans) return SWARM_ERR_SHAPE;
+  if (g.K % DBK || g.lda % 8 || g.ldb % 8 || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return SWARM_ERR_SHAPE;
+  KArgs k;
+  k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
+  k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
+  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;
+  if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {
+    k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
+    return launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);
+  }
+  if (g.M % 128 == 0 && g.N % 128 == 0) {
+    k.tiles_m = g.M / 128; k.tiles_n = g.N / 128;
+    return launch_dma_layout<128, 128, 2, 2>(k, g.a_trans, g.b_trans, st);
+  }
+  return SWARM_ERR_SHAPE;
+}
+
+}  // namespace swarm
