@@ -238,6 +238,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   auto al16 = [](const void* q) { return ((uintptr_t)q & 15) == 0; };
   bool vec_ok = (g.lda % 8 == 0) && (g.ldb % 8 == 0) && al16(g.A) && al16(g.B) &&
                 (g.a_trans ? g.M % 8 == 0 : g.K % 8 == 0) && (g.b_trans ? g.N % 8 == 0 : g.K % 8 == 0);
+  if (g.epilogue == EPI_ACCUM_F32) vec_ok = vec_ok && g.N % 4 == 0 && g.ldc % 4 == 0 && al16(g.C);
   if (g.epilogue != EPI_ACCUM_F32)   // the bf16 epilogue moves 8-element chunks
     vec_ok = vec_ok && g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.bias || al16(g.bias)) &&
              (!g.aux || (al16(g.aux) && g.ldaux % 8 == 0)) && (!g.C2 || (al16(g.C2) && g.ldc2 % 8 == 0));
@@ -248,6 +249,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
     if (s != SWARM_ERR_SHAPE) return s;
   }
   KArgs k;
+  k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;

@@ -19,6 +19,7 @@ struct KArgs {
   const bf16_raw* bias; const bf16_raw* aux; int ldaux;
   bf16_raw* C2; int ldc2;
   int tiles_m, tiles_n;
+  int group_m;   // tile rows walked together (L2 reuse of the B panel)
 };
 
 // Launch order maps consecutive workgroups to the 8 XCDs round-robin; give every XCD a contiguous band
@@ -27,7 +28,7 @@ __device__ __forceinline__ void tile_of_block(const KArgs& p, int& tile_m, int& 
   int pid = blockIdx.x;
   const int ntiles = p.tiles_m * p.tiles_n;
   if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
-  constexpr int GM = 8;
+  const int GM = p.group_m;
   const int per_group = GM * p.tiles_n;
   const int group = pid / per_group;
   const int first_m = group * GM;
@@ -68,27 +69,38 @@ template <int FM, int FN, bool GUARD>
 __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][FN], int row0, int col0, int l32,
                                               int lg, float* stage) {
   const int epi = p.epilogue;
+  constexpr int COLS = 32 * FN;
+  const int lane = l32 + 32 * lg;
   if (epi == EPI_ACCUM_F32) {
+    // C (fp32) += acc, 16 bytes per lane: 16 lanes cover one 64-column row of the sub-tile
+    constexpr int LPR4 = COLS / 4, RPP4 = 64 / LPR4;
     float* c = reinterpret_cast<float*>(p.C);
+    const int c4 = lane % LPR4, rsub4 = lane / LPR4;
+    const int colf = col0 + 4 * c4;
+    const bool colf_ok = !GUARD || colf < p.N;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int col = col0 + j * 32 + l32;
-      if (GUARD && col >= p.N) continue;
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row0 + i * 32 + 8 * (r >> 2) + 4 * lg + (r & 3);
-          if (GUARD && row >= p.M) continue;
-          c[(size_t)row * p.ldc + col] += acc[i][j][r];
-        }
+        for (int r = 0; r < 16; ++r)
+          stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+#pragma unroll
+      for (int ps = 0; ps < 32 / RPP4; ++ps) {
+        const int rl = ps * RPP4 + rsub4;
+        const int row = row0 + i * 32 + rl;
+        const float4 v = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 4 * c4);
+        if (!colf_ok || (GUARD && row >= p.M)) continue;
+        float4* dst = reinterpret_cast<float4*>(c + (size_t)row * p.ldc + colf);
+        float4 o = *dst;
+        o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        *dst = o;
+      }
     }
     return;
   }
-  constexpr int COLS = 32 * FN;
   constexpr int LPR = COLS / 8;          // lanes per row on the way out
   constexpr int RPP = 64 / LPR;          // rows per pass
-  const int lane = l32 + 32 * lg;
   const int c8 = lane % LPR, rsub = lane / LPR;
   const int col = col0 + 8 * c8;
   const bool col_ok = !GUARD || col < p.N;     // N is a multiple of 8, so a chunk is all in or all out

@@ -8,11 +8,15 @@
 //
 //   operand with k contiguous in memory  : LDS tile [rows][32 k] (64-byte rows), fragment = one
 //                                          ds_read_b128 per 32x16 operand block;
-//   operand with k as the slow index     : LDS tile [32 k][rows] exactly as in memory, fragment = two
+//   operand with k as the slow index     : LDS tile [k][rows] exactly as in memory, fragment = two
 //   (W in dgrad, both operands in wgrad)   ds_read_b64_tr_b16 (the LDS transpose read hands lane n the
-//                                          four k-consecutive values of column n).
+//                                          four k-consecutive values of column n).  One pass of that
+//                                          read serves 32 lanes = 4 k-rows x 64 bytes; rows alias in the
+//                                          banks, so 32-byte pairs are XOR-ed with 2*(k-row & 3).
 //
 // One workgroup owns one output tile and walks K in order: deterministic.
+#include <cstdlib>
+
 #include "gemm_bf16_common.h"
 
 namespace swarm {
@@ -63,7 +67,7 @@ __device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int l
     } else {
       constexpr int CPR = BR / 8;           // 16-byte chunks per k-row
       const int krow = q * (64 / CPR) + lane / CPR;
-      const int chunk = (lane % CPR) ^ (2 * (krow & 3));
+      const int chunk = (lane % CPR) ^ (4 * (krow & 3));
       src = g + (size_t)(k0 + krow) * ld + r0 + chunk * 8;
     }
     __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds + q * 512), 16, 0, 0);
@@ -84,7 +88,7 @@ __device__ __forceinline__ bf16x8 frag_trans(const bf16_raw* tile, int col_base,
   const int lg = grp >> 1;
   const int col = col_base + 16 * (grp & 1) + 4 * (l16 & 3);
   const int kq = l16 >> 2;                                   // k-row inside the group of four
-  const int chunk = (col >> 3) ^ (2 * kq);
+  const int chunk = (col >> 3) ^ (4 * kq);
   const int off = chunk * 8 + (col & 4);
   const int krow = 16 * kk + 8 * lg + kq;
   const bf16_raw* p0 = tile + krow * BR + off;
@@ -211,6 +215,7 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   if (g.a_trans && !g.b_trans) return SWARM_ERR_SHAPE;
   if (g.K % DBK || g.lda % 8 || g.ldb % 8 || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return SWARM_ERR_SHAPE;
   KArgs k;
+  k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;
