@@ -1,16 +1,20 @@
 // Causal flash attention for bf16 on gfx950 MFMA (v_mfma_f32_32x32x16_bf16), forward and backward.
 //
-// All kernels compute score tiles TRANSPOSED where that puts the softmax row in one lane:
+// Score tiles are computed TRANSPOSED where that puts the softmax row in one lane:
 //   forward / dq:  S^T[kv][q] = K Q^T, so a lane owns one query column, its 16+16 kv values sit in
 //                  its own registers and in lane^32: row max / row sum cost one cross-lane step, the
 //                  online-softmax rescale of O^T[dh][q] is lane-local, and P^T (resp. dS^T) is already
 //                  in the B-operand layout of the next MFMA (O^T = V^T P^T, dQ^T = K^T dS^T).
 //   dk/dv:         S[q][kv] = Q K^T, so a lane owns one key column and P / dS are in the B-operand
 //                  layout of dV^T = dO^T P and dK^T = Q^T dS.
-// The operand that must be read along the contraction index (V^T, K^T, Q^T, dO^T) is transposed in
-// registers on its way into LDS (8 x 4 patches, 8-byte global loads, 16-byte LDS rows); the 8 slots
-// of a 16-byte LDS row follow the accumulator's row order {4g..4g+3, 8+4g..8+4g+3}, so one 16-byte
-// LDS read feeds one MFMA.
+//
+// Tiles of 64 rows x d_head go from global memory straight into LDS (global_load_lds_dwordx4, two
+// stages, no staging registers) in their memory layout.  A tile is read in two ways:
+//   rows as MFMA rows      (contraction along d_head): one ds_read_b128 per operand block;
+//   rows as the contraction (V^T, K^T, Q^T, dO^T)    : two ds_read_b64_tr_b16 (LDS transpose read),
+//     whose row bases follow the accumulator's row order {4g..4g+3, 8+4g..8+4g+3}.
+// One XOR swizzle of the 16-byte chunks (swz) keeps both kinds of read bank-conflict free.
+// Rows past the sequence end are loaded from the last valid row; the causal mask zeroes them.
 //
 // Deterministic: dq and dk/dv come from two kernels that each own their output rows (no atomics).
 #include "kernels.h"
@@ -22,11 +26,16 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short i16x4;
 
 constexpr int kThreads = 256;   // 4 wavefronts
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ int swz8(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }    // vmcnt(0) only
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   f32x2 v = {a, b};
@@ -40,101 +49,99 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& p, int base) {
   return __builtin_bit_cast(bf16x8, u);
 }
 
-__device__ __forceinline__ bf16x8 lds_frag(const bf16_raw* p) {
-  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+// ---- 64 x DH tiles in LDS -----------------------------------------------------------------------
+// chunk swizzle.  DH = 128 (256-byte rows): a 16-lane b128 pass reads 16 consecutive rows -> needs a
+// bijection of row&15; a 32-lane transpose-read pass reads rows r..r+3 x four adjacent chunks ->
+// bits [3:2] must separate rows r..r+3.  DH = 64 (128-byte rows): same idea with 8 chunks per row.
+template <int DH>
+__device__ __forceinline__ int swz(int row) {
+  if constexpr (DH == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  const int x = (row >> 1) & 7;
+  return ((x & 1) << 2) | (x >> 1);
 }
 
-// ---- tile movers ------------------------------------------------------------------------------
-// Row-major tile [ROWS][DH] (contraction along DH): 16-byte chunks, chunk index XOR (row & 7).
-template <int ROWS, int DH>
-struct RowTile {
-  static constexpr int CH = DH / 8;
-  static constexpr int NI = ROWS * CH / kThreads;
-  uint4 r[NI];
-  // src points at element (row 0, col 0) of the tile's matrix; row pitch ld; rows >= nrows read as zero
-  __device__ __forceinline__ void load(const bf16_raw* __restrict__ src, int ld, int row0, int nrows, int tid) {
+template <int DH>
+struct Tile64 {
+  static constexpr int CH = DH / 8;          // 16-byte chunks per row
+  static constexpr int RPI = 64 / CH;        // rows filled by one load instruction (1 KiB)
+  static constexpr int NINST = CH;           // instructions per tile
+  static constexpr int ELEMS = 64 * DH;
+
+  // src = element (row 0, col 0) of the matrix; rows >= nrows are taken from row nrows-1
+  static __device__ __forceinline__ void issue(const bf16_raw* __restrict__ src, int ld, int row0, int nrows,
+                                               bf16_raw* lds, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int it = tid + i * kThreads;
-      const int row = it / CH, chunk = it % CH;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * ld + chunk * 8);
-      r[i] = v;
+    for (int t = 0; t < NINST / 4; ++t) {
+      const int q = wave + 4 * t;
+      const int r = q * RPI + lane / CH;
+      const int chunk = (lane % CH) ^ swz<DH>(r);
+      const int grow = min(row0 + r, nrows - 1);
+      __builtin_amdgcn_global_load_lds(GLB_PTR(src + (size_t)grow * ld + chunk * 8), LDS_PTR(lds + q * 512), 16, 0,
+                                       0);
     }
   }
-  __device__ __forceinline__ void store(bf16_raw* __restrict__ lds, int tid) const {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int it = tid + i * kThreads;
-      const int row = it / CH, chunk = it % CH;
-      *reinterpret_cast<uint4*>(lds + row * DH + ((chunk ^ (row & 7)) << 3)) = r[i];
-    }
+  // operand block with tile rows as MFMA rows: lane l32 -> row, 8 contraction values from chunk
+  static __device__ __forceinline__ bf16x8 rows(const bf16_raw* tile, int row, int chunk) {
+    return __builtin_bit_cast(bf16x8,
+                              *reinterpret_cast<const uint4*>(tile + row * DH + ((chunk ^ swz<DH>(row)) << 3)));
   }
-  static __device__ __forceinline__ int frag_off(int row, int chunk) {
-    return row * DH + ((chunk ^ (row & 7)) << 3);
+  // operand block with tile rows as the contraction: MFMA row = column cbase + (lane & 31); the 8 contraction
+  // slots of lane group lg are tile rows rbase + 4*lg + {0..3} and rbase + 8 + 4*lg + {0..3}
+  static __device__ __forceinline__ bf16x8 cols(const bf16_raw* tile, int cbase, int rbase, int lane) {
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int col = cbase + 16 * (grp & 1) + 4 * (l16 & 3);
+    const int r0 = rbase + 4 * (grp >> 1) + (l16 >> 2);
+    const int r1 = r0 + 8;
+    const bf16_raw* p0 = tile + r0 * DH + (((col >> 3) ^ swz<DH>(r0)) << 3) + (col & 4);
+    const bf16_raw* p1 = tile + r1 * DH + (((col >> 3) ^ swz<DH>(r1)) << 3) + (col & 4);
+    const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p0);
+    const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p1);
+    const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+    return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
   }
 };
 
-// Transposed tile: memory [64 rows (contraction index)][DH]  ->  LDS [DH][64], where 16-byte chunk
-// c = 2t+g of an LDS row holds contraction rows {16t+4g..+3, 16t+8+4g..+3} (accumulator row order).
-template <int DH>
-struct TransTile {
-  static constexpr int NP = 8 * (DH / 4);                 // patches
-  static constexpr int NI = (NP + kThreads - 1) / kThreads;
-  uint2 r[NI][8];
-  __device__ __forceinline__ void load(const bf16_raw* __restrict__ src, int ld, int row0, int nrows, int tid) {
+// 8 contraction values of row `row` (columns col ..) straight from global memory, zero past nrows
+__device__ __forceinline__ bf16x8 global_frag(const bf16_raw* base, int ld, int row, int nrows, int col) {
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < nrows) v = *reinterpret_cast<const uint4*>(base + (size_t)row * ld + col);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int N>
+__device__ __forceinline__ void zero(f32x16 (&a)[N]) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int it = tid + i * kThreads;
-      const int dc = it % (DH / 4), c = it / (DH / 4);
-      const int base = 16 * (c >> 1) + 4 * (c & 1);
+  for (int i = 0; i < N; ++i)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int row = row0 + base + (j < 4 ? j : j + 4);
-        uint2 v = make_uint2(0, 0);
-        if (it < NP && row < nrows) v = *reinterpret_cast<const uint2*>(src + (size_t)row * ld + dc * 4);
-        r[i][j] = v;
-      }
+    for (int r = 0; r < 16; ++r) a[i][r] = 0.f;
+}
+
+// store a transposed accumulator (acc[i][r] = value at dh = 32i + 8(r/4) + 4lg + r%4 of this lane's row)
+template <int DB>
+__device__ __forceinline__ void store_rowT(bf16_raw* row, const f32x16 (&acc)[DB], float mul, int lg) {
+#pragma unroll
+  for (int i = 0; i < DB; ++i)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 v;
+      v.x = pack2(acc[i][4 * g + 0] * mul, acc[i][4 * g + 1] * mul);
+      v.y = pack2(acc[i][4 * g + 2] * mul, acc[i][4 * g + 3] * mul);
+      *reinterpret_cast<uint2*>(row + 32 * i + 8 * g + 4 * lg) = v;
     }
-  }
-  __device__ __forceinline__ void store(bf16_raw* __restrict__ lds, int tid) const {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int it = tid + i * kThreads;
-      if (it >= NP) continue;
-      const int dc = it % (DH / 4), c = it / (DH / 4);
-      const uint2* q = r[i];
-      uint4 o0, o1, o2, o3;
-      o0.x = __builtin_amdgcn_perm(q[1].x, q[0].x, 0x05040100u); o1.x = __builtin_amdgcn_perm(q[1].x, q[0].x, 0x07060302u);
-      o0.y = __builtin_amdgcn_perm(q[3].x, q[2].x, 0x05040100u); o1.y = __builtin_amdgcn_perm(q[3].x, q[2].x, 0x07060302u);
-      o0.z = __builtin_amdgcn_perm(q[5].x, q[4].x, 0x05040100u); o1.z = __builtin_amdgcn_perm(q[5].x, q[4].x, 0x07060302u);
-      o0.w = __builtin_amdgcn_perm(q[7].x, q[6].x, 0x05040100u); o1.w = __builtin_amdgcn_perm(q[7].x, q[6].x, 0x07060302u);
-      o2.x = __builtin_amdgcn_perm(q[1].y, q[0].y, 0x05040100u); o3.x = __builtin_amdgcn_perm(q[1].y, q[0].y, 0x07060302u);
-      o2.y = __builtin_amdgcn_perm(q[3].y, q[2].y, 0x05040100u); o3.y = __builtin_amdgcn_perm(q[3].y, q[2].y, 0x07060302u);
-      o2.z = __builtin_amdgcn_perm(q[5].y, q[4].y, 0x05040100u); o3.z = __builtin_amdgcn_perm(q[5].y, q[4].y, 0x07060302u);
-      o2.w = __builtin_amdgcn_perm(q[7].y, q[6].y, 0x05040100u); o3.w = __builtin_amdgcn_perm(q[7].y, q[6].y, 0x07060302u);
-      const int row = dc * 4;
-      *reinterpret_cast<uint4*>(lds + frag_off(row + 0, c)) = o0;
-      *reinterpret_cast<uint4*>(lds + frag_off(row + 1, c)) = o1;
-      *reinterpret_cast<uint4*>(lds + frag_off(row + 2, c)) = o2;
-      *reinterpret_cast<uint4*>(lds + frag_off(row + 3, c)) = o3;
-    }
-  }
-  static __device__ __forceinline__ int frag_off(int row, int chunk) {
-    return row * 64 + ((chunk ^ swz8(row)) << 3);
-  }
-};
+}
 
 // ---- forward ------------------------------------------------------------------------------------
 // grid (ceil(S/128), H, B); wavefront w owns query rows q0+32w .. q0+32w+31; KV tiles of 64.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const bf16_raw* __restrict__ qkv,
-                                                            bf16_raw* __restrict__ o, float* __restrict__ lse,
-                                                            int S, int H) {
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* __restrict__ qkv,
+                                                               bf16_raw* __restrict__ o, float* __restrict__ lse,
+                                                               int S, int H) {
+  using T = Tile64<DH>;
   constexpr int KS = DH / 16, DB = DH / 32;
-  constexpr int STAGE = 2 * 64 * DH;
-  extern __shared__ __attribute__((aligned(16))) bf16_raw lds[];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lg = lane >> 5;
+  constexpr int STAGE = 2 * T::ELEMS;
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int d = H * DH, ld = 3 * d;
   const int q0 = qt * 128;
@@ -146,54 +153,38 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const bf16_raw* __re
   const int qrow = q0 + 32 * w + l32;
   bf16x8 qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (qrow < S) v = *reinterpret_cast<const uint4*>(Q + (size_t)qrow * ld + 16 * ks + 8 * lg);
-    qf[ks] = __builtin_bit_cast(bf16x8, v);
-  }
+  for (int ks = 0; ks < KS; ++ks) qf[ks] = global_frag(Q, ld, qrow, S, 16 * ks + 8 * lg);
 
   f32x16 oacc[DB];
-#pragma unroll
-  for (int i = 0; i < DB; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  zero(oacc);
   float m = -INFINITY, l = 0.f;
 
-  const int kv_end = min(S, q0 + 128);
-  const int ntile = (kv_end + 63) / 64;
-  RowTile<64, DH> kt;
-  TransTile<DH> vt;
-  kt.load(K, ld, 0, S, tid);
-  vt.load(V, ld, 0, S, tid);
-  kt.store(lds, tid);
-  vt.store(lds + 64 * DH, tid);
-  __syncthreads();
+  const int ntile = (min(S, q0 + 128) + 63) / 64;
+  auto issue = [&](int t) {
+    bf16_raw* st = lds + (t & 1) * STAGE;
+    T::issue(K, ld, t * 64, S, st, w, lane);
+    T::issue(V, ld, t * 64, S, st + T::ELEMS, w, lane);
+  };
+  issue(0);
+  wait_vm0();
+  __builtin_amdgcn_s_barrier();
 
   const int wq_min = q0 + 32 * w, wq_max = wq_min + 31;
   for (int t = 0; t < ntile; ++t) {
     const bf16_raw* sK = lds + (t & 1) * STAGE;
-    const bf16_raw* sV = sK + 64 * DH;
+    const bf16_raw* sV = sK + T::ELEMS;
     const int kv0 = t * 64;
-    const bool more = t + 1 < ntile;
-    if (more) {
-      kt.load(K, ld, kv0 + 64, S, tid);
-      vt.load(V, ld, kv0 + 64, S, tid);
-    }
+    if (t + 1 < ntile) issue(t + 1);
     if (kv0 <= wq_max) {
       f32x16 s[2];
+      zero(s);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 a = lds_frag(sK + RowTile<64, DH>::frag_off(32 * kb + l32, 2 * ks + lg));
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
-        }
-      }
-      if (kv0 + 63 > wq_min) {   // tile touches the diagonal: mask kv > q
+        for (int kb = 0; kb < 2; ++kb)
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sK, 32 * kb + l32, 2 * ks + lg), qf[ks], s[kb], 0,
+                                                          0, 0);
+      if (kv0 + 63 > wq_min) {   // tile touches the diagonal (or the sequence end): mask kv > q
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -233,50 +224,20 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const bf16_raw* __re
 #pragma unroll
       for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-          const bf16x8 a = lds_frag(sV + TransTile<DH>::frag_off(32 * i + l32, 2 * tt + lg));
-          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], oacc[i], 0, 0, 0);
-        }
+        for (int tt = 0; tt < 4; ++tt)
+          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sV, 32 * i, 16 * tt, lane), pf[tt], oacc[i], 0, 0,
+                                                            0);
     }
-    if (more) {
-      bf16_raw* dK = lds + ((t + 1) & 1) * STAGE;
-      kt.store(dK, tid);
-      vt.store(dK + 64 * DH, tid);
-    }
-    __syncthreads();
+    wait_vm0();
+    wait_lgkm0();
+    __builtin_amdgcn_s_barrier();
   }
 
   if (qrow < S) {
-    const float inv = 1.0f / l;
-    bf16_raw* orow = o + ((size_t)b * S + qrow) * d + h * DH;
-#pragma unroll
-    for (int i = 0; i < DB; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 v;
-        v.x = pack2(oacc[i][4 * g + 0] * inv, oacc[i][4 * g + 1] * inv);
-        v.y = pack2(oacc[i][4 * g + 2] * inv, oacc[i][4 * g + 3] * inv);
-        *reinterpret_cast<uint2*>(orow + 32 * i + 8 * g + 4 * lg) = v;
-      }
+    store_rowT<DB>(o + ((size_t)b * S + qrow) * d + h * DH, oacc, 1.0f / l, lg);
     if (lg == 0) lse[((size_t)b * H + h) * S + qrow] = m * (c / kLog2e) + logf(l);
   }
 }
-
-template <int DH>
-swarm_status launch_fwd(const bf16_raw* qkv, bf16_raw* o, float* lse, int B, int S, int H, hipStream_t st) {
-  constexpr size_t lds_bytes = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
-  auto kern = attn_fwd_kernel<DH>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
-        hipSuccess)
-      return SWARM_ERR_LAUNCH;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3((S + 127) / 128, H, B), dim3(kThreads), lds_bytes, st, qkv, o, lse, S, H);
-  return launch_status();
-}
-
 
 // ---- backward -----------------------------------------------------------------------------------
 // delta[b,h,s] = sum_c dO[s, h, c] * O[s, h, c].  One workgroup per token; a head's dh/8 chunks sit in
@@ -307,16 +268,17 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16_raw* __
 
 // dK, dV: grid (ceil(S/128), H, B); wavefront w owns key rows kv0+32w..+31; query tiles of 64.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(const bf16_raw* __restrict__ qkv,
-                                                                 const bf16_raw* __restrict__ dout,
-                                                                 const float* __restrict__ lse,
-                                                                 const float* __restrict__ delta,
-                                                                 bf16_raw* __restrict__ dqkv, int S, int H) {
+__global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_kernel(const bf16_raw* __restrict__ qkv,
+                                                                    const bf16_raw* __restrict__ dout,
+                                                                    const float* __restrict__ lse,
+                                                                    const float* __restrict__ delta,
+                                                                    bf16_raw* __restrict__ dqkv, int S, int H) {
+  using T = Tile64<DH>;
   constexpr int KS = DH / 16, DB = DH / 32;
-  constexpr int TILE = 64 * DH;                 // elements of one 64-row tile
-  constexpr int STAGE = 4 * TILE + 256;         // Q, Q^T, dO, dO^T + (lse, delta) as 2 x 64 floats
-  extern __shared__ __attribute__((aligned(16))) bf16_raw lds[];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lg = lane >> 5;
+  constexpr int STAGE = 2 * T::ELEMS + 256;     // Q, dO + (lse, delta) as 2 x 64 floats
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int d = H * DH, ld = 3 * d;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
@@ -332,73 +294,47 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(const bf16_raw*
   bf16x8 kf[KS], vf[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    uint4 a = make_uint4(0, 0, 0, 0), v = make_uint4(0, 0, 0, 0);
-    if (kvrow < S) {
-      a = *reinterpret_cast<const uint4*>(K + (size_t)kvrow * ld + 16 * ks + 8 * lg);
-      v = *reinterpret_cast<const uint4*>(V + (size_t)kvrow * ld + 16 * ks + 8 * lg);
-    }
-    kf[ks] = __builtin_bit_cast(bf16x8, a);
-    vf[ks] = __builtin_bit_cast(bf16x8, v);
+    kf[ks] = global_frag(K, ld, kvrow, S, 16 * ks + 8 * lg);
+    vf[ks] = global_frag(V, ld, kvrow, S, 16 * ks + 8 * lg);
   }
   f32x16 dvacc[DB], dkacc[DB];
-#pragma unroll
-  for (int i = 0; i < DB; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dvacc[i][r] = 0.f; dkacc[i][r] = 0.f; }
+  zero(dvacc);
+  zero(dkacc);
 
   const int t_begin = (kb * 128) / 64, t_end = (S + 63) / 64;
-  RowTile<64, DH> qt, dot;
-  TransTile<DH> qtt, dott;
-  float stat = 0.f;   // threads 0..63: lse of row tid; 64..127: delta of row tid-64
-  auto load_tile = [&](int q0) {
-    qt.load(Q, ld, q0, S, tid);
-    qtt.load(Q, ld, q0, S, tid);
-    dot.load(dO, d, q0, S, tid);
-    dott.load(dO, d, q0, S, tid);
-    if (tid < 128) {
-      const int row = q0 + (tid & 63);
-      stat = row < S ? (tid < 64 ? lse_r[row] : del_r[row]) : 0.f;
+  auto issue = [&](int t) {
+    bf16_raw* st = lds + ((t - t_begin) & 1) * STAGE;
+    T::issue(Q, ld, t * 64, S, st, w, lane);
+    T::issue(dO, d, t * 64, S, st + T::ELEMS, w, lane);
+    if (w < 2) {   // wavefront 0: lse of the tile's 64 rows, wavefront 1: delta
+      const int row = min(t * 64 + lane, S - 1);
+      __builtin_amdgcn_global_load_lds(GLB_PTR((w == 0 ? lse_r : del_r) + row),
+                                       LDS_PTR(st + 2 * T::ELEMS + w * 128), 4, 0, 0);
     }
   };
-  auto store_tile = [&](bf16_raw* st) {
-    qt.store(st, tid);
-    qtt.store(st + TILE, tid);
-    dot.store(st + 2 * TILE, tid);
-    dott.store(st + 3 * TILE, tid);
-    if (tid < 128) reinterpret_cast<float*>(st + 4 * TILE)[tid] = stat;
-  };
-  load_tile(t_begin * 64);
-  store_tile(lds);
-  __syncthreads();
+  issue(t_begin);
+  wait_vm0();
+  __builtin_amdgcn_s_barrier();
 
   const int wkv_min = kb * 128 + 32 * w;
   for (int t = t_begin; t < t_end; ++t) {
     const bf16_raw* sQ = lds + ((t - t_begin) & 1) * STAGE;
-    const bf16_raw* sQt = sQ + TILE;
-    const bf16_raw* sdO = sQ + 2 * TILE;
-    const bf16_raw* sdOt = sQ + 3 * TILE;
-    const float* sstat = reinterpret_cast<const float*>(sQ + 4 * TILE);
+    const bf16_raw* sdO = sQ + T::ELEMS;
+    const float* sstat = reinterpret_cast<const float*>(sQ + 2 * T::ELEMS);
     const int q0 = t * 64;
-    const bool more = t + 1 < t_end;
-    if (more) load_tile(q0 + 64);
+    if (t + 1 < t_end) issue(t + 1);
     if (q0 + 63 >= wkv_min) {
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[qb][r] = 0.f; dp[qb][r] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-          const bf16x8 a = lds_frag(sQ + RowTile<64, DH>::frag_off(32 * qb + l32, 2 * ks + lg));
-          s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[ks], s[qb], 0, 0, 0);
-          const bf16x8 g = lds_frag(sdO + RowTile<64, DH>::frag_off(32 * qb + l32, 2 * ks + lg));
-          dp[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g, vf[ks], dp[qb], 0, 0, 0);
-        }
       const bool diag = q0 < wkv_min + 32;   // some q in the tile is below some kv of this wavefront
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sQ, 32 * qb + l32, 2 * ks + lg), kf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sdO, 32 * qb + l32, 2 * ks + lg), vf[ks], dp, 0, 0, 0);
+        }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int rbase = 32 * qb + 8 * g + 4 * lg;
@@ -408,63 +344,55 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dkdv_kernel(const bf16_raw*
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[qb][r], c, -Ls[e] * kLog2e));
+            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[e] * kLog2e));
             const int q = q0 + rbase + e;
             if ((diag && kvrow > q) || q >= S) p = 0.f;
-            s[qb][r] = p;
-            dp[qb][r] = p * (dp[qb][r] - Ds[e]);
+            s[r] = p;
+            dp[r] = p * (dp[r] - Ds[e]);
           }
         }
-      bf16x8 pf[4], dsf[4];
+        bf16x8 pf[2], dsf[2];
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) {
-        pf[tt] = pack8(s[tt >> 1], 8 * (tt & 1));
-        dsf[tt] = pack8(dp[tt >> 1], 8 * (tt & 1));
-      }
-#pragma unroll
-      for (int i = 0; i < DB; ++i)
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-          const bf16x8 a = lds_frag(sdOt + TransTile<DH>::frag_off(32 * i + l32, 2 * tt + lg));
-          dvacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[tt], dvacc[i], 0, 0, 0);
-          const bf16x8 a2 = lds_frag(sQt + TransTile<DH>::frag_off(32 * i + l32, 2 * tt + lg));
-          dkacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2, dsf[tt], dkacc[i], 0, 0, 0);
+        for (int tt = 0; tt < 2; ++tt) {
+          pf[tt] = pack8(s, 8 * tt);
+          dsf[tt] = pack8(dp, 8 * tt);
         }
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            dvacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sdO, 32 * i, 32 * qb + 16 * tt, lane), pf[tt],
+                                                               dvacc[i], 0, 0, 0);
+            dkacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sQ, 32 * i, 32 * qb + 16 * tt, lane), dsf[tt],
+                                                               dkacc[i], 0, 0, 0);
+          }
+      }
     }
-    if (more) store_tile(lds + ((t + 1 - t_begin) & 1) * STAGE);
-    __syncthreads();
+    wait_vm0();
+    wait_lgkm0();
+    __builtin_amdgcn_s_barrier();
   }
 
   if (kvrow < S) {
     bf16_raw* dkrow = dqkv + ((size_t)b * S + kvrow) * ld + d + h * DH;
-    bf16_raw* dvrow = dkrow + d;
-#pragma unroll
-    for (int i = 0; i < DB; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 v;
-        v.x = pack2(dkacc[i][4 * g + 0] * scale, dkacc[i][4 * g + 1] * scale);
-        v.y = pack2(dkacc[i][4 * g + 2] * scale, dkacc[i][4 * g + 3] * scale);
-        *reinterpret_cast<uint2*>(dkrow + 32 * i + 8 * g + 4 * lg) = v;
-        v.x = pack2(dvacc[i][4 * g + 0], dvacc[i][4 * g + 1]);
-        v.y = pack2(dvacc[i][4 * g + 2], dvacc[i][4 * g + 3]);
-        *reinterpret_cast<uint2*>(dvrow + 32 * i + 8 * g + 4 * lg) = v;
-      }
+    store_rowT<DB>(dkrow, dkacc, scale, lg);
+    store_rowT<DB>(dkrow + d, dvacc, 1.0f, lg);
   }
 }
 
 // dQ: grid (ceil(S/128), H, B); wavefront w owns query rows q0+32w..+31; KV tiles of 64.
 template <int DH>
-__global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(const bf16_raw* __restrict__ qkv,
-                                                               const bf16_raw* __restrict__ dout,
-                                                               const float* __restrict__ lse,
-                                                               const float* __restrict__ delta,
-                                                               bf16_raw* __restrict__ dqkv, int S, int H) {
+__global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw* __restrict__ qkv,
+                                                                  const bf16_raw* __restrict__ dout,
+                                                                  const float* __restrict__ lse,
+                                                                  const float* __restrict__ delta,
+                                                                  bf16_raw* __restrict__ dqkv, int S, int H) {
+  using T = Tile64<DH>;
   constexpr int KS = DH / 16, DB = DH / 32;
-  constexpr int TILE = 64 * DH;
-  constexpr int STAGE = 3 * TILE;               // K, V, K^T
-  extern __shared__ __attribute__((aligned(16))) bf16_raw lds[];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lg = lane >> 5;
+  constexpr int STAGE = 2 * T::ELEMS;           // K, V
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qtile = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int d = H * DH, ld = 3 * d;
   const int q0 = qtile * 128;
@@ -479,13 +407,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(const bf16_raw* _
   bf16x8 qf[KS], dof[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    uint4 a = make_uint4(0, 0, 0, 0), g = make_uint4(0, 0, 0, 0);
-    if (qrow < S) {
-      a = *reinterpret_cast<const uint4*>(Q + (size_t)qrow * ld + 16 * ks + 8 * lg);
-      g = *reinterpret_cast<const uint4*>(dO + (size_t)qrow * d + 16 * ks + 8 * lg);
-    }
-    qf[ks] = __builtin_bit_cast(bf16x8, a);
-    dof[ks] = __builtin_bit_cast(bf16x8, g);
+    qf[ks] = global_frag(Q, ld, qrow, S, 16 * ks + 8 * lg);
+    dof[ks] = global_frag(dO, d, qrow, S, 16 * ks + 8 * lg);
   }
   float L2 = 0.f, dl = 0.f;
   if (qrow < S) {
@@ -493,92 +416,60 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_dq_kernel(const bf16_raw* _
     dl = delta[((size_t)b * H + h) * S + qrow];
   }
   f32x16 dqacc[DB];
-#pragma unroll
-  for (int i = 0; i < DB; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dqacc[i][r] = 0.f;
+  zero(dqacc);
 
-  const int kv_end = min(S, q0 + 128);
-  const int ntile = (kv_end + 63) / 64;
-  RowTile<64, DH> kt, vt;
-  TransTile<DH> ktt;
-  kt.load(K, ld, 0, S, tid);
-  vt.load(V, ld, 0, S, tid);
-  ktt.load(K, ld, 0, S, tid);
-  kt.store(lds, tid);
-  vt.store(lds + TILE, tid);
-  ktt.store(lds + 2 * TILE, tid);
-  __syncthreads();
+  const int ntile = (min(S, q0 + 128) + 63) / 64;
+  auto issue = [&](int t) {
+    bf16_raw* st = lds + (t & 1) * STAGE;
+    T::issue(K, ld, t * 64, S, st, w, lane);
+    T::issue(V, ld, t * 64, S, st + T::ELEMS, w, lane);
+  };
+  issue(0);
+  wait_vm0();
+  __builtin_amdgcn_s_barrier();
 
   const int wq_min = q0 + 32 * w, wq_max = wq_min + 31;
   for (int t = 0; t < ntile; ++t) {
     const bf16_raw* sK = lds + (t & 1) * STAGE;
-    const bf16_raw* sV = sK + TILE;
-    const bf16_raw* sKt = sK + 2 * TILE;
+    const bf16_raw* sV = sK + T::ELEMS;
     const int kv0 = t * 64;
-    const bool more = t + 1 < ntile;
-    if (more) {
-      kt.load(K, ld, kv0 + 64, S, tid);
-      vt.load(V, ld, kv0 + 64, S, tid);
-      ktt.load(K, ld, kv0 + 64, S, tid);
-    }
+    if (t + 1 < ntile) issue(t + 1);
     if (kv0 <= wq_max) {
-      f32x16 s[2], dp[2];
-#pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[kb2][r] = 0.f; dp[kb2][r] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
-          const bf16x8 a = lds_frag(sK + RowTile<64, DH>::frag_off(32 * kb2 + l32, 2 * ks + lg));
-          s[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb2], 0, 0, 0);
-          const bf16x8 v = lds_frag(sV + RowTile<64, DH>::frag_off(32 * kb2 + l32, 2 * ks + lg));
-          dp[kb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, dof[ks], dp[kb2], 0, 0, 0);
-        }
       const bool diag = kv0 + 63 > wq_min;
 #pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
+      for (int kb2 = 0; kb2 < 2; ++kb2) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sK, 32 * kb2 + l32, 2 * ks + lg), qf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sV, 32 * kb2 + l32, 2 * ks + lg), dof[ks], dp, 0, 0, 0);
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[kb2][r], c, -L2));
+          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -L2));
           const int kv = kv0 + 32 * kb2 + 8 * (r >> 2) + 4 * lg + (r & 3);
           if (diag && kv > qrow) p = 0.f;
-          dp[kb2][r] = p * (dp[kb2][r] - dl);
+          dp[r] = p * (dp[r] - dl);
         }
-      bf16x8 dsf[4];
+        bf16x8 dsf[2];
 #pragma unroll
-      for (int tt = 0; tt < 4; ++tt) dsf[tt] = pack8(dp[tt >> 1], 8 * (tt & 1));
+        for (int tt = 0; tt < 2; ++tt) dsf[tt] = pack8(dp, 8 * tt);
 #pragma unroll
-      for (int i = 0; i < DB; ++i)
+        for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-          const bf16x8 a = lds_frag(sKt + TransTile<DH>::frag_off(32 * i + l32, 2 * tt + lg));
-          dqacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[tt], dqacc[i], 0, 0, 0);
-        }
+          for (int tt = 0; tt < 2; ++tt)
+            dqacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sK, 32 * i, 32 * kb2 + 16 * tt, lane), dsf[tt],
+                                                               dqacc[i], 0, 0, 0);
+      }
     }
-    if (more) {
-      bf16_raw* dK = lds + ((t + 1) & 1) * STAGE;
-      kt.store(dK, tid);
-      vt.store(dK + TILE, tid);
-      ktt.store(dK + 2 * TILE, tid);
-    }
-    __syncthreads();
+    wait_vm0();
+    wait_lgkm0();
+    __builtin_amdgcn_s_barrier();
   }
 
-  if (qrow < S) {
-    bf16_raw* dqrow = dqkv + ((size_t)b * S + qrow) * ld + h * DH;
-#pragma unroll
-    for (int i = 0; i < DB; ++i)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 v;
-        v.x = pack2(dqacc[i][4 * g + 0] * scale, dqacc[i][4 * g + 1] * scale);
-        v.y = pack2(dqacc[i][4 * g + 2] * scale, dqacc[i][4 * g + 3] * scale);
-        *reinterpret_cast<uint2*>(dqrow + 32 * i + 8 * g + 4 * lg) = v;
-      }
-  }
+  if (qrow < S) store_rowT<DB>(dqkv + ((size_t)b * S + qrow) * ld + h * DH, dqacc, scale, lg);
 }
 
 template <typename Kern>
@@ -592,10 +483,20 @@ swarm_status set_lds(Kern kern, size_t bytes, bool& done) {
 }
 
 template <int DH>
+swarm_status launch_fwd(const bf16_raw* qkv, bf16_raw* o, float* lse, int B, int S, int H, hipStream_t st) {
+  constexpr size_t lds_bytes = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
+  static bool a0 = false;
+  if (set_lds(attn_fwd_kernel<DH>, lds_bytes, a0) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((S + 127) / 128, H, B), dim3(kThreads), lds_bytes, st, qkv, o, lse,
+                     S, H);
+  return launch_status();
+}
+
+template <int DH>
 swarm_status launch_bwd(const bf16_raw* qkv, const bf16_raw* o, const bf16_raw* dout, const float* lse, float* delta,
                         bf16_raw* dqkv, int B, int S, int H, hipStream_t st) {
-  constexpr size_t lds_dkdv = (size_t)2 * (4 * 64 * DH + 256) * sizeof(bf16_raw);
-  constexpr size_t lds_dq = (size_t)2 * 3 * 64 * DH * sizeof(bf16_raw);
+  constexpr size_t lds_dkdv = (size_t)2 * (2 * 64 * DH + 256) * sizeof(bf16_raw);
+  constexpr size_t lds_dq = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
   static bool a1 = false, a2 = false;
   if (set_lds(attn_bwd_dkdv_kernel<DH>, lds_dkdv, a1) != SWARM_OK) return SWARM_ERR_LAUNCH;
   if (set_lds(attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
