@@ -138,12 +138,12 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
         for (int e = 0; e < 8; ++e) x[e] += bias[e];
         if (p.C2) *reinterpret_cast<uint4*>(p.C2 + (size_t)row * p.ldc2 + col) = pack8_bf16(x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = gelu_f(x[e]);
+        for (int e = 0; e < 8; ++e) x[e] = gelu_fast(x[e]);
       } else if (epi == EPI_DGELU) {
         float a[8];
         unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_f(a[e]);
+        for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_fast(a[e]);
       }
       *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + col) = pack8_bf16(x);
     }

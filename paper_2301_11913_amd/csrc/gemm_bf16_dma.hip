@@ -1,12 +1,12 @@
 // bf16 MFMA GEMM, pipelined variant for tile-aligned shapes:  C[M,N] (+)= sum_k A(m,k) B(n,k).
 //
 // Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes per lane,
-// no staging registers) through a ring of NS stages of K-depth 32, so NS-1 slices are in flight: an
-// HBM miss takes longer than one slice of MFMA work, and every K slice is new to the L2.
+// no staging registers) through a ring of NS stages of K-depth DBK, so NS-1 slices are in flight while
+// one is multiplied.
 // A load instruction fills 1 KiB of contiguous LDS; which 16-byte global chunk a lane fetches is free,
 // which gives the bank-conflict-avoiding XOR swizzles below for nothing.
 //
-//   operand with k contiguous in memory  : LDS tile [rows][32 k] (64-byte rows), fragment = one
+//   operand with k contiguous in memory  : LDS tile [rows][DBK k], fragment = one
 //                                          ds_read_b128 per 32x16 operand block;
 //   operand with k as the slow index     : LDS tile [k][rows] exactly as in memory, fragment = two
 //   (W in dgrad, both operands in wgrad)   ds_read_b64_tr_b16 (the LDS transpose read hands lane n the
@@ -24,14 +24,8 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 
-#ifndef EXP_DBK
-#define EXP_DBK 64
-#endif
-#ifndef EXP_NS
-#define EXP_NS 2
-#endif
-constexpr int DBK = EXP_DBK;   // K depth of a stage (32 or 64)
-constexpr int NS = EXP_NS;     // LDS stages
+constexpr int DBK = 64;        // K depth of a stage (32 or 64; 64 measured faster: full 128-byte lines per row)
+constexpr int NS = 2;          // LDS stages (NS x (BM+BN) x DBK x 2 bytes must fit 160 KiB)
 constexpr int KCH = DBK / 8;   // 16-byte chunks per row of a non-transposed tile
 
 // chunk swizzle of a non-transposed tile: makes the 16 rows that one LDS pass reads (64 banks x 4 B)
@@ -138,12 +132,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
 
   for (int kt = 0; kt < KT; ++kt) {
     const bool steady = kt + NS - 1 < KT;
-#ifndef EXP_NOLOAD
     if (steady) issue(kt + NS - 1);     // refills the stage that was read in iteration kt-1
-#endif
     const bf16_raw* sA = lds + (kt % NS) * STAGE;
     const bf16_raw* sB = sA + BM * DBK;
-#ifndef EXP_LOADONLY
 #pragma unroll
     for (int kk = 0; kk < DBK / 16; ++kk) {
       bf16x8 a[FM], b[FN];
@@ -160,24 +151,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-#ifndef EXP_NOMFMA
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-#else
-          acc[i][j][0] += __builtin_bit_cast(float, __builtin_bit_cast(uint4, a[i]).x ^ __builtin_bit_cast(uint4, b[j]).y);
-#endif
-        }
+        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-#endif
     // slice kt+1 must have landed (this wavefront's part), then all wavefronts meet: everybody's part of
     // slice kt+1 is visible and everybody is done reading slice kt
-#ifndef EXP_NOLOAD
     if (steady) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
-#endif
     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS reads of slice kt are complete
-#ifndef EXP_NOBARRIER
     __builtin_amdgcn_s_barrier();
-#endif
   }
 
   // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
