@@ -68,6 +68,7 @@ __device__ __forceinline__ uint4 pack8_bf16(const float (&x)[8]) {
 template <int FM, int FN, bool GUARD>
 __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][FN], int row0, int col0, int l32,
                                               int lg, float* stage) {
+  static_assert(32 * FN <= kEpiPitch - 4, "the LDS patch holds 64 columns");
   const int epi = p.epilogue;
   constexpr int COLS = 32 * FN;
   const int lane = l32 + 32 * lg;

@@ -1,0 +1,91 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (same shapes, same kernels).  bf16 tolerance 2e-2 max-normalised, codec bit-exact.
+
+The 8192-token end-to-end configuration is too large for the oracle as a whole, so there the oracle
+computes one sequence of the microbatch (sequences do not interact in x_out / grad_in), and the parameter
+gradients are checked (a) against the oracle for that sequence alone and (b) through the accumulation
+property: the full-microbatch gradients equal the sum of the per-sequence ones.
+"""
+import numpy as np
+import pytest
+import torch
+
+import swarm_synth as synth
+from oracle import codec as ocodec
+from stage_util import run_gpu, run_oracle, compare, max_norm_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+@pytest.mark.parametrize("name", ["width_bf16_d1024", "width_bf16_d2048", "width_bf16_d4096"])
+def test_width_sweep_block(name):
+    wl = synth.WORKLOADS[name]
+    params, x, G = synth.make_params(wl), synth.make_x_in(wl), synth.make_grad_out(wl)
+    gpu = run_gpu(wl, params, x, G)
+    ref = run_oracle(wl, params, x, G, dt=np.float64 if wl.d_model < 4096 else np.float32)
+    errs, bad = compare(gpu, ref, TOL)
+    print(name, {k: "%.2e" % v for k, v in errs.items()})
+    assert not bad, bad
+
+
+def test_shared4_stage():
+    wl = synth.WORKLOADS["shared4_bf16_d4096"]
+    params, x, G = synth.make_params(wl), synth.make_x_in(wl), synth.make_grad_out(wl)
+    gpu = run_gpu(wl, params, x, G)
+    ref = run_oracle(wl, params, x, G, dt=np.float32)
+    errs, bad = compare(gpu, ref, TOL)
+    print(wl.name, {k: "%.2e" % v for k, v in errs.items()})
+    assert not bad, bad
+
+
+def test_end_to_end_stage_with_codec():
+    import paper_2301_11913_amd as sw
+    wl = synth.WORKLOADS["e2e_bf16_d4096"]
+    params = synth.make_params(wl)
+    x_src, g_src = synth.make_x_in(wl), synth.make_grad_out(wl)
+    # stage boundary: inputs arrive int8-encoded; the GPU decodes them (bit-exact against the oracle)
+    n = x_src.size
+    cx, sx = ocodec.encode(x_src.reshape(-1))
+    cg, sg = ocodec.encode(g_src.reshape(-1))
+    xd = torch.empty(x_src.shape, dtype=torch.bfloat16, device="cuda")
+    gd = torch.empty(x_src.shape, dtype=torch.bfloat16, device="cuda")
+    sw.swarm_codec_decode(torch.from_numpy(cx).cuda(), torch.from_numpy(sx).cuda(), xd)
+    sw.swarm_codec_decode(torch.from_numpy(cg).cuda(), torch.from_numpy(sg).cuda(), gd)
+    x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(x_src.shape)
+    G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(x_src.shape)
+    assert np.array_equal(xd.float().cpu().numpy(), x) and np.array_equal(gd.float().cpu().numpy(), G)
+    del xd, gd
+
+    full = run_gpu(wl, params, x, G)
+    # (1) one sequence against the oracle: x_out, grad_in and that sequence's parameter gradients
+    one = wl.replace(batch=1)
+    ref0 = run_oracle(one, params, x[:1], G[:1], dt=np.float32)
+    gpu0 = run_gpu(one, params, x[:1], G[:1])
+    errs, bad = compare(gpu0, ref0, TOL)
+    print("sequence 0", {k: "%.2e" % v for k, v in errs.items()})
+    assert not bad, bad
+    assert max_norm_err(full["x_out"][:1], ref0["x_out"]) <= TOL
+    assert max_norm_err(full["grad_in"][:1], ref0["grad_in"]) <= TOL
+    # sequences are independent: the full run reproduces the single-sequence run bit for bit
+    assert np.array_equal(full["x_out"][:1], gpu0["x_out"]) and np.array_equal(full["grad_in"][:1], gpu0["grad_in"])
+    # (2) accumulation: full-microbatch gradients = sum over sequences
+    tot = [{k: v.copy() for k, v in g.items()} for g in gpu0["grads"]]
+    for b in range(1, wl.batch):
+        gb = run_gpu(one, params, x[b:b + 1], G[b:b + 1], forward=False)
+        for l in range(wl.n_layers):
+            for k in tot[l]:
+                tot[l][k] += gb["grads"][l][k]
+        assert np.array_equal(full["grad_in"][b:b + 1], gb["grad_in"])
+    for l in range(wl.n_layers):
+        for k in tot[l]:
+            assert max_norm_err(full["grads"][l][k], tot[l][k]) <= 1e-4, (l, k)
+    # (3) stage exit: encode x_out and grad_in on the GPU, bit-exact against the oracle codec on the same bits
+    for key in ("x_out", "grad_in"):
+        t = torch.from_numpy(full[key].astype(np.float32)).to(torch.bfloat16).cuda()
+        codes = torch.empty(n, dtype=torch.int8, device="cuda")
+        scales = torch.empty(n // 64, dtype=torch.float32, device="cuda")
+        sw.swarm_codec_encode(t, codes, scales)
+        torch.cuda.synchronize()
+        rc, rs = ocodec.encode(full[key].astype(np.float32).reshape(-1))
+        assert np.array_equal(rc, codes.cpu().numpy()) and np.array_equal(rs, scales.cpu().numpy())
