@@ -23,6 +23,16 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 
 
+def measured_traffic(workload):
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary (None if there is none)."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_%s_hbm_traffic.json" % workload)
+    try:
+        with open(path) as f:
+            return json.load(f)["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def model_flops(wl):
     """Paper convention (Table 6: 6 * parameters * tokens for fwd+bwd) plus the causal attention term."""
     T, d, f, S, B = wl.tokens, wl.d_model, wl.d_ffn, wl.seq, wl.batch
@@ -69,6 +79,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="e2e_bf16_d4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library is the per-peer, single-GPU path of a SWARM stage; peers of a stage share "
@@ -151,10 +163,18 @@ def main():
         achieved = tot_fl / (tot_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": round(achieved, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": None, "launches_per_step": launches // args.steps,
+                    "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
                     "avg_launch_us": round(tot_ms * 1e3 / launches, 1),
                     "flops_per_launch": tot_fl / launches,
                     "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
     out = {"metric": "stage fwd+bwd tokens/s (+ int8 boundary codec)", "value": round(tokens_per_s, 1),

@@ -1,0 +1,65 @@
+"""Summarise rocprofv3 CSV output of a bench.py run.
+
+    python -m paper_2301_11913_amd.profile_summary stats  <dir>/<prefix>_kernel_stats.csv
+    python -m paper_2301_11913_amd.profile_summary pmc    <fetch>_counter_collection.csv <write>_counter_collection.csv
+
+`pmc` expects two runs of `bench.py --copy-calibration` under `rocprofv3 --pmc FETCH_SIZE` and
+`--pmc WRITE_SIZE`.  The counters are scaled by what they read for the plain 1 GiB device copies of
+that run (each reads 2^30 and writes 2^30 bytes), then averaged over the launches of the bf16 GEMM kernels.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import json
+import sys
+
+GIB = float(1 << 30)
+
+
+def _short(name: str) -> str:
+    return name.replace("swarm::(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+
+
+def stats(path: str) -> None:
+    rows = list(csv.DictReader(open(path)))
+    print("| kernel | calls | avg us | total ms | % |")
+    print("|---|---|---|---|---|")
+    g_ns, g_calls = 0.0, 0
+    for r in rows:
+        if float(r["Percentage"]) < 0.05:
+            continue
+        n = _short(r["Name"])
+        print("| `%s` | %s | %.1f | %.2f | %.1f |" % (n, r["Calls"], float(r["AverageNs"]) / 1e3,
+                                                    float(r["TotalDurationNs"]) / 1e6, float(r["Percentage"])))
+        if n.startswith("gemm_bf16"):
+            g_ns += float(r["TotalDurationNs"])
+            g_calls += int(r["Calls"])
+    if g_calls:
+        print("\nAll bf16 GEMM kernels: %d calls, average %.1f us per launch." % (g_calls, g_ns / g_calls / 1e3))
+
+
+def _per_kernel(path: str, counter: str):
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        if r["Counter_Name"] == counter:
+            acc[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
+    return acc
+
+
+def pmc(fetch_csv: str, write_csv: str) -> None:
+    out = {}
+    for counter, path in (("FETCH_SIZE", fetch_csv), ("WRITE_SIZE", write_csv)):
+        acc = _per_kernel(path, counter)
+        copies = [v for k, vals in acc.items() if "copy" in k.lower() or "Copy" in k for v in vals]
+        big = [v for v in copies if v > 0.5 * max(copies)]          # the 1 GiB calibration copies
+        per_unit = GIB / (sum(big) / len(big))                      # bytes per counter unit
+        gemm = [v for k, vals in acc.items() if k.startswith("gemm_bf16") for v in vals]
+        out[counter] = {"calibration_copies": len(big), "bytes_per_counter_unit": per_unit,
+                        "gemm_launches": len(gemm), "gemm_bytes_per_launch": per_unit * sum(gemm) / len(gemm)}
+    out["hbm_bytes_per_launch"] = out["FETCH_SIZE"]["gemm_bytes_per_launch"] + out["WRITE_SIZE"]["gemm_bytes_per_launch"]
+    print(json.dumps(out, indent=1))
+
+
+if __name__ == "__main__":
+    {"stats": stats, "pmc": pmc}[sys.argv[1]](*sys.argv[2:])
