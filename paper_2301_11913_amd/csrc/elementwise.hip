@@ -17,6 +17,16 @@ constexpr int kLnRowsPerBlock = 16;          // backward: rows per workgroup
 
 template <typename T> struct V8;
 template <> struct V8<bf16_raw> {
+  struct Raw { uint4 v; };                   // 8 elements as loaded (keeps register use low)
+  static __device__ __forceinline__ Raw load_raw(const bf16_raw* p) { return Raw{*reinterpret_cast<const uint4*>(p)}; }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
+    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+  }
   static __device__ __forceinline__ void load(const bf16_raw* p, float (&x)[8]) {
     uint4 v = *reinterpret_cast<const uint4*>(p);
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -34,6 +44,13 @@ template <> struct V8<bf16_raw> {
   }
 };
 template <> struct V8<float> {
+  struct Raw { float4 a, b; };
+  static __device__ __forceinline__ Raw load_raw(const float* p) {
+    return Raw{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
+  }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w; x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+  }
   static __device__ __forceinline__ void load(const float* p, float (&x)[8]) {
     float4 a = *reinterpret_cast<const float4*>(p);
     float4 b = *reinterpret_cast<const float4*>(p + 4);
@@ -97,92 +114,106 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
   }
 }
 
-// Backward.  Each wavefront walks kLnRowsPerBlock / 4 rows, keeps per-lane partial sums of
-// dgamma / dbeta, and the four wavefronts combine them through LDS in wave order.
-// partial: [gridDim.x][2][d] floats (dgamma then dbeta).
-template <typename T, int NIT>
+// Backward.  The four wavefronts of a workgroup split the COLUMNS of a row (a quarter each), so a lane
+// carries only d/256 dgamma / dbeta partial sums; the two row statistics are combined across the
+// wavefronts through LDS, four rows per barrier.  A workgroup walks kLnRowsPerBlock rows and writes its
+// column partials to partial[gridDim.x][2][d] (dgamma then dbeta); a fixed-order second stage adds them up.
+constexpr int kLnBatch = 4;                  // rows per barrier
+template <typename T, int NITQ>
 __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                             const float* __restrict__ mean,
                                                             const float* __restrict__ rstd,
                                                             const T* __restrict__ gamma, const T* __restrict__ dres,
                                                             T* __restrict__ dx, float* __restrict__ partial, int rows,
                                                             int d) {
-  extern __shared__ float lds_part[];          // [2][d]
+  __shared__ float red[2][kLnBatch][kLnWaves][2];
+  typedef typename V8<T>::Raw Raw;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int nchunk = d >> 3;
+  const int cq = d >> 5;                       // chunks per wavefront (a quarter of d/8)
+  const int cbase = wave * cq;
   const float inv_d = 1.0f / (float)d;
-  float g[NIT][8], pg[NIT][8], pb[NIT][8];
+  Raw graw[NITQ];
+  float pg[NITQ][8], pb[NITQ][8];
 #pragma unroll
-  for (int it = 0; it < NIT; ++it) {
+  for (int it = 0; it < NITQ; ++it) {
     const int c = lane + it * 64;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { pg[it][i] = 0.f; pb[it][i] = 0.f; g[it][i] = 0.f; }
-    if (c < nchunk) V8<T>::load(gamma + c * 8, g[it]);
+    for (int i = 0; i < 8; ++i) { pg[it][i] = 0.f; pb[it][i] = 0.f; }
+    graw[it] = V8<T>::load_raw(gamma + (size_t)(cbase + (c < cq ? c : 0)) * 8);
   }
   const int row0 = blockIdx.x * kLnRowsPerBlock;
-  for (int rr = wave; rr < kLnRowsPerBlock; rr += kLnWaves) {
-    const int row = row0 + rr;
-    if (row >= rows) break;
-    const float mu = mean[row], r = rstd[row];
-    float xh[NIT][8], t[NIT][8];
-    float s1 = 0.f, s2 = 0.f;
+  for (int b0 = 0; b0 < kLnRowsPerBlock; b0 += kLnBatch) {
+    const int par = (b0 / kLnBatch) & 1;
+    Raw xraw[kLnBatch][NITQ], dyraw[kLnBatch][NITQ];
+    float mu[kLnBatch], rs[kLnBatch];
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int c = lane + it * 64;
-      if (c < nchunk) {
-        float xv[8], dv[8];
-        V8<T>::load(x + (size_t)row * d + c * 8, xv);
-        V8<T>::load(dy + (size_t)row * d + c * 8, dv);
+    for (int r = 0; r < kLnBatch; ++r) {
+      const int row = row0 + b0 + r;
+      float s1 = 0.f, s2 = 0.f;
+      mu[r] = 0.f; rs[r] = 0.f;
+      if (row < rows) {
+        mu[r] = mean[row]; rs[r] = rstd[row];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          xh[it][i] = (xv[i] - mu) * r;
-          t[it][i] = dv[i] * g[it][i];
-          s1 += t[it][i];
-          s2 += t[it][i] * xh[it][i];
-          pg[it][i] += dv[i] * xh[it][i];
-          pb[it][i] += dv[i];
-        }
-      }
-    }
-    const float m1 = wave_sum(s1) * inv_d;
-    const float m2 = wave_sum(s2) * inv_d;
+        for (int it = 0; it < NITQ; ++it) {
+          const int c = lane + it * 64;
+          if (c < cq) {
+            xraw[r][it] = V8<T>::load_raw(x + (size_t)row * d + (size_t)(cbase + c) * 8);
+            dyraw[r][it] = V8<T>::load_raw(dy + (size_t)row * d + (size_t)(cbase + c) * 8);
+            float xv[8], dv[8], g[8];
+            V8<T>::unpack(xraw[r][it], xv);
+            V8<T>::unpack(dyraw[r][it], dv);
+            V8<T>::unpack(graw[it], g);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int c = lane + it * 64;
-      if (c < nchunk) {
-        float rs[8], o[8];
-        V8<T>::load(dres + (size_t)row * d + c * 8, rs);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = rs[i] + r * (t[it][i] - m1 - xh[it][i] * m2);
-        V8<T>::store(dx + (size_t)row * d + c * 8, o);
-      }
-    }
-  }
-  // fixed-order combine: wave 0 stores, waves 1..3 add in turn
-  for (int w = 0; w < kLnWaves; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int c = lane + it * 64;
-        if (c < nchunk) {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            if (w == 0) {
-              lds_part[c * 8 + i] = pg[it][i];
-              lds_part[d + c * 8 + i] = pb[it][i];
-            } else {
-              lds_part[c * 8 + i] += pg[it][i];
-              lds_part[d + c * 8 + i] += pb[it][i];
+            for (int i = 0; i < 8; ++i) {
+              const float xh = (xv[i] - mu[r]) * rs[r];
+              const float t = dv[i] * g[i];
+              s1 += t;
+              s2 += t * xh;
+              pg[it][i] += dv[i] * xh;
+              pb[it][i] += dv[i];
             }
           }
         }
       }
+      s1 = wave_sum(s1);
+      s2 = wave_sum(s2);
+      if (lane == 0) { red[par][r][wave][0] = s1; red[par][r][wave][1] = s2; }
     }
-    __syncthreads();
+    __syncthreads();   // the other parity's slots are rewritten only after the next barrier
+#pragma unroll
+    for (int r = 0; r < kLnBatch; ++r) {
+      const int row = row0 + b0 + r;
+      if (row >= rows) continue;
+      const float m1 = (((red[par][r][0][0] + red[par][r][1][0]) + red[par][r][2][0]) + red[par][r][3][0]) * inv_d;
+      const float m2 = (((red[par][r][0][1] + red[par][r][1][1]) + red[par][r][2][1]) + red[par][r][3][1]) * inv_d;
+#pragma unroll
+      for (int it = 0; it < NITQ; ++it) {
+        const int c = lane + it * 64;
+        if (c < cq) {
+          float res[8], o[8], xv[8], dv[8], g[8];
+          V8<T>::load(dres + (size_t)row * d + (size_t)(cbase + c) * 8, res);
+          V8<T>::unpack(xraw[r][it], xv);
+          V8<T>::unpack(dyraw[r][it], dv);
+          V8<T>::unpack(graw[it], g);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = res[i] + rs[r] * (dv[i] * g[i] - m1 - (xv[i] - mu[r]) * rs[r] * m2);
+          V8<T>::store(dx + (size_t)row * d + (size_t)(cbase + c) * 8, o);
+        }
+      }
+    }
   }
   float* out = partial + (size_t)blockIdx.x * 2 * d;
-  for (int i = threadIdx.x; i < 2 * d; i += kLnThreads) out[i] = lds_part[i];
+#pragma unroll
+  for (int it = 0; it < NITQ; ++it) {
+    const int c = lane + it * 64;
+    if (c < cq) {
+      *reinterpret_cast<float4*>(out + (size_t)(cbase + c) * 8) = make_float4(pg[it][0], pg[it][1], pg[it][2], pg[it][3]);
+      *reinterpret_cast<float4*>(out + (size_t)(cbase + c) * 8 + 4) = make_float4(pg[it][4], pg[it][5], pg[it][6], pg[it][7]);
+      *reinterpret_cast<float4*>(out + d + (size_t)(cbase + c) * 8) = make_float4(pb[it][0], pb[it][1], pb[it][2], pb[it][3]);
+      *reinterpret_cast<float4*>(out + d + (size_t)(cbase + c) * 8 + 4) = make_float4(pb[it][4], pb[it][5], pb[it][6], pb[it][7]);
+    }
+  }
 }
 
 // Stage 1 of a column sum: workgroup = 64 column chunks (512 columns) x 4 row groups over kCsRows rows.
@@ -225,8 +256,17 @@ __global__ __launch_bounds__(256) void reduce_rows_accum_kernel(const float* __r
   const int per = (P + 3) / 4;
   const int p0 = rg * per, p1 = min(P, p0 + per);
   float s = 0.f;
-  if (c < C)
-    for (int p = p0; p < p1; ++p) s += partial[(size_t)p * stride + c];
+  if (c < C) {
+    // eight independent running sums (fixed assignment p mod 8, fixed combine order) keep loads in flight
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += partial[(size_t)(p + u) * stride + c];
+    }
+    for (int u = 0; p < p1; ++p, ++u) a[u] += partial[(size_t)p * stride + c];
+    s = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  }
   red[rg][threadIdx.x & 63] = s;
   __syncthreads();
   if (rg == 0 && c < C) {
@@ -256,15 +296,12 @@ template <typename T>
 swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const float* rstd, const T* g,
                              const T* dres, T* dx, float* partial, int rows, int d, hipStream_t st) {
   const int grid = (rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
-  const size_t lds = (size_t)2 * d * sizeof(float);
-#define LN_BWD(NIT)                                                                                          \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NIT>), dim3(grid), dim3(kLnThreads), lds, st, dy, x, mean, rstd, g, \
+#define LN_BWD(NITQ)                                                                                        \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
                      dres, dx, partial, rows, d)
-  if (d <= 512) LN_BWD(1);
-  else if (d <= 1024) LN_BWD(2);
-  else if (d <= 2048) LN_BWD(4);
-  else if (d <= 4096) LN_BWD(8);
-  else if (d <= 8192) LN_BWD(16);
+  if (d <= 2048) LN_BWD(1);
+  else if (d <= 4096) LN_BWD(2);
+  else if (d <= 8192) LN_BWD(4);
   else return SWARM_ERR_SHAPE;
 #undef LN_BWD
   return launch_status();
