@@ -266,19 +266,24 @@ __global__ __launch_bounds__(kThreads) void attn_delta_kernel(const bf16_raw* __
   }
 }
 
-// dK, dV: grid (ceil(S/128), H, B); wavefront w owns key rows kv0+32w..+31; query tiles of 64.
+// dK, dV: grid (ceil(S/128), H, B), 8 wavefronts.  Wavefronts w and w+4 both own key rows kv0+32w..+31;
+// the first computes dV (S -> P, dV^T += dO^T P), the second dK (S, dP -> dS, dK^T += Q^T dS), so each holds
+// one 32 x d_head accumulator and two wavefronts fit a SIMD.  Both read the same Q / dO tiles of 64 queries.
+constexpr int kDkDvThreads = 512;
 template <int DH>
-__global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_kernel(const bf16_raw* __restrict__ qkv,
-                                                                    const bf16_raw* __restrict__ dout,
-                                                                    const float* __restrict__ lse,
-                                                                    const float* __restrict__ delta,
-                                                                    bf16_raw* __restrict__ dqkv, int S, int H) {
+__global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_raw* __restrict__ qkv,
+                                                                     const bf16_raw* __restrict__ dout,
+                                                                     const float* __restrict__ lse,
+                                                                     const float* __restrict__ delta,
+                                                                     bf16_raw* __restrict__ dqkv, int S, int H) {
   using T = Tile64<DH>;
   constexpr int KS = DH / 16, DB = DH / 32;
   constexpr int STAGE = 2 * T::ELEMS + 256;     // Q, dO + (lse, delta) as 2 x 64 floats
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w = w8 & 3;
+  const bool is_dk = w8 >= 4;
   const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int d = H * DH, ld = 3 * d;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
@@ -295,21 +300,20 @@ __global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_k
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     kf[ks] = global_frag(K, ld, kvrow, S, 16 * ks + 8 * lg);
-    vf[ks] = global_frag(V, ld, kvrow, S, 16 * ks + 8 * lg);
+    vf[ks] = is_dk ? global_frag(V, ld, kvrow, S, 16 * ks + 8 * lg) : kf[ks];
   }
-  f32x16 dvacc[DB], dkacc[DB];
-  zero(dvacc);
-  zero(dkacc);
+  f32x16 acc[DB];     // dV^T or dK^T
+  zero(acc);
 
   const int t_begin = (kb * 128) / 64, t_end = (S + 63) / 64;
   auto issue = [&](int t) {
     bf16_raw* st = lds + ((t - t_begin) & 1) * STAGE;
-    T::issue(Q, ld, t * 64, S, st, w, lane);
-    T::issue(dO, d, t * 64, S, st + T::ELEMS, w, lane);
-    if (w < 2) {   // wavefront 0: lse of the tile's 64 rows, wavefront 1: delta
+    if (!is_dk) T::issue(Q, ld, t * 64, S, st, w, lane);
+    else T::issue(dO, d, t * 64, S, st + T::ELEMS, w, lane);
+    if (w == 0) {   // wavefront 0: lse of the tile's 64 rows, wavefront 4: delta
       const int row = min(t * 64 + lane, S - 1);
-      __builtin_amdgcn_global_load_lds(GLB_PTR((w == 0 ? lse_r : del_r) + row),
-                                       LDS_PTR(st + 2 * T::ELEMS + w * 128), 4, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLB_PTR((is_dk ? del_r : lse_r) + row),
+                                       LDS_PTR(st + 2 * T::ELEMS + (is_dk ? 128 : 0)), 4, 0, 0);
     }
   };
   issue(t_begin);
@@ -333,7 +337,8 @@ __global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_k
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sQ, 32 * qb + l32, 2 * ks + lg), kf[ks], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sdO, 32 * qb + l32, 2 * ks + lg), vf[ks], dp, 0, 0, 0);
+          if (is_dk)
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sdO, 32 * qb + l32, 2 * ks + lg), vf[ks], dp, 0, 0, 0);
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -347,25 +352,19 @@ __global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_k
             float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[e] * kLog2e));
             const int q = q0 + rbase + e;
             if ((diag && kvrow > q) || q >= S) p = 0.f;
-            s[r] = p;
-            dp[r] = p * (dp[r] - Ds[e]);
+            s[r] = is_dk ? p * (dp[r] - Ds[e]) : p;      // dS for the dK wavefront, P for the dV wavefront
           }
         }
-        bf16x8 pf[2], dsf[2];
+        bf16x8 bf[2];
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          pf[tt] = pack8(s, 8 * tt);
-          dsf[tt] = pack8(dp, 8 * tt);
-        }
+        for (int tt = 0; tt < 2; ++tt) bf[tt] = pack8(s, 8 * tt);
+        const bf16_raw* src = is_dk ? sQ : sdO;
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            dvacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sdO, 32 * i, 32 * qb + 16 * tt, lane), pf[tt],
-                                                               dvacc[i], 0, 0, 0);
-            dkacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sQ, 32 * i, 32 * qb + 16 * tt, lane), dsf[tt],
-                                                               dkacc[i], 0, 0, 0);
-          }
+          for (int tt = 0; tt < 2; ++tt)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(src, 32 * i, 32 * qb + 16 * tt, lane), bf[tt],
+                                                             acc[i], 0, 0, 0);
       }
     }
     wait_vm0();
@@ -375,8 +374,8 @@ __global__ __launch_bounds__(kThreads, (DH == 128 ? 1 : 2)) void attn_bwd_dkdv_k
 
   if (kvrow < S) {
     bf16_raw* dkrow = dqkv + ((size_t)b * S + kvrow) * ld + d + h * DH;
-    store_rowT<DB>(dkrow, dkacc, scale, lg);
-    store_rowT<DB>(dkrow + d, dvacc, 1.0f, lg);
+    if (is_dk) store_rowT<DB>(dkrow, acc, scale, lg);
+    else store_rowT<DB>(dkrow + d, acc, 1.0f, lg);
   }
 }
 
@@ -502,7 +501,8 @@ swarm_status launch_bwd(const bf16_raw* qkv, const bf16_raw* o, const bf16_raw* 
   if (set_lds(attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3(B * S), dim3(kThreads), 0, st, o, dout, delta, S, H);
   dim3 grid((S + 127) / 128, H, B);
-  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, grid, dim3(kThreads), lds_dkdv, st, qkv, dout, lse, delta, dqkv, S, H);
+  hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, grid, dim3(kDkDvThreads), lds_dkdv, st, qkv, dout, lse, delta, dqkv, S,
+                     H);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, grid, dim3(kThreads), lds_dq, st, qkv, dout, lse, delta, dqkv, S, H);
   return launch_status();
 }
