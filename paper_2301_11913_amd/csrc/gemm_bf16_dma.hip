@@ -130,35 +130,54 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   if (KT >= NS - 1) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 
+  constexpr int KK = DBK / 16;
+  static_assert(NS == 2 && KK % 2 == 0, "the fragment pipeline below assumes two stages and an even slice depth");
+  auto load_frags = [&](const bf16_raw* sA, const bf16_raw* sB, int kk, bf16x8 (&a)[FM], bf16x8 (&b)[FN]) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      if constexpr (A_T) a[i] = frag_trans<BM>(sA, wm * WTM + i * 32, kk, lane);
+      else a[i] = frag_rows(sA, wm * WTM + i * 32, kk, l32, lg);
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      if constexpr (B_T) b[j] = frag_trans<BN>(sB, wn * WTN + j * 32, kk, lane);
+      else b[j] = frag_rows(sB, wn * WTN + j * 32, kk, l32, lg);
+    }
+  };
+  auto mma = [&](const bf16x8 (&a)[FM], const bf16x8 (&b)[FN]) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+
+  // Software pipeline: the fragments of sub-step kk+1 are read while sub-step kk is multiplied, and the
+  // last sub-step of a slice is multiplied AFTER the barrier, behind the reads of the next slice's
+  // first fragments, so the matrix pipe has work queued across the barrier.
+  bf16x8 fa[2][FM], fb[2][FN];
+  load_frags(lds, lds + BM * DBK, 0, fa[0], fb[0]);
   for (int kt = 0; kt < KT; ++kt) {
-    const bool steady = kt + NS - 1 < KT;
-    if (steady) issue(kt + NS - 1);     // refills the stage that was read in iteration kt-1
-    const bf16_raw* sA = lds + (kt % NS) * STAGE;
+    const bool more = kt + 1 < KT;
+    if (more) issue(kt + 1);            // refills the stage whose reads all completed before the last barrier
+    const bf16_raw* sA = lds + (kt & 1) * STAGE;
     const bf16_raw* sB = sA + BM * DBK;
 #pragma unroll
-    for (int kk = 0; kk < DBK / 16; ++kk) {
-      bf16x8 a[FM], b[FN];
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        if constexpr (A_T) a[i] = frag_trans<BM>(sA, wm * WTM + i * 32, kk, lane);
-        else a[i] = frag_rows(sA, wm * WTM + i * 32, kk, l32, lg);
-      }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        if constexpr (B_T) b[j] = frag_trans<BN>(sB, wn * WTN + j * 32, kk, lane);
-        else b[j] = frag_rows(sB, wn * WTN + j * 32, kk, l32, lg);
-      }
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    for (int kk = 0; kk + 1 < KK; ++kk) {
+      load_frags(sA, sB, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+      mma(fa[kk & 1], fb[kk & 1]);
     }
-    // slice kt+1 must have landed (this wavefront's part), then all wavefronts meet: everybody's part of
-    // slice kt+1 is visible and everybody is done reading slice kt
-    if (steady) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wavefront's LDS reads of slice kt are complete
+    // slice kt+1 must have landed (this wavefront's part) and this wavefront's reads of slice kt be complete;
+    // then all wavefronts meet
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();
+    if (more) {
+      const bf16_raw* nA = lds + ((kt + 1) & 1) * STAGE;
+      load_frags(nA, nA + BM * DBK, 0, fa[0], fb[0]);
+    }
+    mma(fa[(KK - 1) & 1], fb[(KK - 1) & 1]);
   }
+  __builtin_amdgcn_s_barrier();   // all MFMAs read registers only, but keep the epilogue's LDS reuse fenced
 
   // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
   gemm_epilogue<FM, FN, false>(p, acc, m0 + wm * WTM, n0 + wn * WTN, l32, lg,
