@@ -161,12 +161,42 @@ def main():
             tot_ms += ms.value; tot_fl += fl.value; launches += nl
         lib.swarm_kernel_timing_enable(0)
         achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": round(achieved, 1),
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
                     "avg_launch_us": round(tot_ms * 1e3 / launches, 1),
                     "flops_per_launch": tot_fl / launches,
                     "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+
+    # codec alone on the boundary tensor, HBM-cold (rotating through > 1 GiB of buffer sets, beyond the
+    # 256 MB last-level cache) and cache-warm (one buffer set); algorithmic bytes: element + code + scale/64
+    codec = None
+    if wl.boundary_codec:
+        es = 2 if wl.dtype == "bf16" else 4
+        byts = n * (es + 1 + 4.0 / 64)
+        nset = max(2, int((1.5 * (1 << 30)) // byts) + 1)
+        xs = [torch.empty(shape, dtype=dt, device=dev).copy_(x_src) for _ in range(nset)]
+        cs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nset)]
+        ss = [torch.empty(n // 64, dtype=torch.float32, device=dev) for _ in range(nset)]
+        codec = {"elements": n, "bytes_per_call": byts, "peak_GBps": 8000.0}
+        for name, fn in (("encode", lambda i: sw.swarm_codec_encode(xs[i], cs[i], ss[i])),
+                         ("decode", lambda i: sw.swarm_codec_decode(cs[i], ss[i], xs[i]))):
+            for mode, idx in (("cold", list(range(nset)) * 3), ("warm", [0] * 50)):
+                for i in idx[:nset]:
+                    fn(i)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in idx:
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / len(idx)
+                codec["%s_%s_us" % (name, mode)] = round(us, 2)
+                codec["%s_%s_GBps" % (name, mode)] = round(byts / us / 1e3, 1)
+        codec["frac_of_hbm_peak_cold"] = {"encode": round(codec["encode_cold_GBps"] / 8000.0, 3),
+                                          "decode": round(codec["decode_cold_GBps"] / 8000.0, 3)}
+        codec["stage_time_over_codec_time"] = round(ms_per_step * 1e3 / (2 * codec["encode_cold_us"] + 2 * codec["decode_cold_us"]), 1)
+        del xs, cs, ss
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -186,7 +216,7 @@ def main():
                       "codec": "int8 absmax block 64 on stage input/output and their gradients"
                       if wl.boundary_codec else "none"},
            "model_tflops_per_s": round(model_flops(wl) / (ms_per_step * 1e-3) / 1e12, 1),
-           "roofline": roofline}
+           "roofline": roofline, "codec": codec}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
