@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="e2e_bf16_d4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused-codec", action="store_true",
+                    help="call swarm_codec_decode/encode around the stage instead of the *_coded entry points")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -113,7 +115,7 @@ def main():
     x_src, g_src = rn(shape, 1.0), rn(shape, wl.grad_sigma)
     cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
                          wl.ln_eps)
-    ws = torch.empty(max(sw.swarm_stage_workspace_bytes(cfg, True), sw.swarm_stage_workspace_bytes(cfg, False)),
+    ws = torch.empty(max(sw.swarm_stage_coded_workspace_bytes(cfg, True), sw.swarm_stage_coded_workspace_bytes(cfg, False)),
                      dtype=torch.uint8, device=dev)
     x, G, y, gin = (torch.empty(shape, dtype=dt, device=dev) for _ in range(4))
     codes = {k: torch.empty(n, dtype=torch.int8, device=dev) for k in ("x", "g", "y", "gin")}
@@ -126,6 +128,12 @@ def main():
         G.copy_(g_src)
 
     def step():
+        if wl.boundary_codec and not args.unfused_codec:
+            # decode / encode fused into the stage's first and last kernels (bit-identical to the separate calls)
+            sw.swarm_stage_forward_coded(cfg, params, codes["x"], scales["x"], x, codes["y"], scales["y"], ws)
+            sw.swarm_stage_backward_coded(cfg, params, x, codes["g"], scales["g"], codes["gin"], scales["gin"], grads,
+                                          ws)
+            return
         if wl.boundary_codec:
             sw.swarm_codec_decode(codes["x"], scales["x"], x)
             sw.swarm_codec_decode(codes["g"], scales["g"], G)
@@ -213,7 +221,8 @@ def main():
            "dtype": wl.dtype, "data": "synthetic",
            "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ffn": wl.d_ffn,
                       "seq": wl.seq, "microbatch": wl.batch, "blocks": wl.n_layers, "repeat": wl.n_repeat,
-                      "codec": "int8 absmax block 64 on stage input/output and their gradients"
+                      "codec": ("int8 absmax block 64 on stage input/output and their gradients, "
+                                + ("separate kernels" if args.unfused_codec else "fused into the stage boundary"))
                       if wl.boundary_codec else "none"},
            "model_tflops_per_s": round(model_flops(wl) / (ms_per_step * 1e-3) / 1e12, 1),
            "roofline": roofline, "codec": codec}

@@ -117,6 +117,27 @@ swarm_status swarm_codec_encode(const void *tensor, int32_t dtype, size_t n_elem
 swarm_status swarm_codec_decode(const int8_t *codes, const float *scales, size_t n_elems, int32_t block,
                                 void *tensor, int32_t dtype, void *hip_stream);
 
+/* The same two stage calls with the 8-bit codec of the "Quantized activations" paragraph fused into the
+ * stage boundary: a peer receives int8-compressed activations / output gradients and sends int8-compressed
+ * outputs / input gradients, so the boundary tensors need not be materialised twice.  Results are
+ * bit-identical to swarm_codec_decode -> swarm_stage_forward / swarm_stage_backward -> swarm_codec_encode
+ * (codec block 64; codes int8 [B*S*d], scales fp32 [B*S*d/64]).
+ *   forward_coded : x_codes/x_scales = encoded stage input; x_dec [B,S,d] receives the decoded input (the
+ *                   caller keeps it as x_in of the backward call); y_codes/y_scales = encoded stage output.
+ *   backward_coded: x_in = decoded stage input; g_codes/g_scales = encoded grad_out;
+ *                   gin_codes/gin_scales = encoded grad_in; grad_params are accumulated into as usual.
+ * Workspace: swarm_stage_coded_workspace_bytes(). */
+size_t swarm_stage_coded_workspace_bytes(const swarm_stage_config *cfg, int for_backward);
+swarm_status swarm_stage_forward_coded(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                       const int8_t *x_codes, const float *x_scales, void *x_dec,
+                                       int8_t *y_codes, float *y_scales,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+swarm_status swarm_stage_backward_coded(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                        const void *x_in, const int8_t *g_codes, const float *g_scales,
+                                        int8_t *gin_codes, float *gin_scales,
+                                        const swarm_block_grads *grad_params,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *swarm_status_string(swarm_status status);
 

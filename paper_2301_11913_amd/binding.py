@@ -11,7 +11,8 @@ SWARM_F32, SWARM_BF16 = 0, 1
 PARAM_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                 "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm_stage_backward",
-                    "swarm_codec_encode", "swarm_codec_decode", "swarm_status_string")
+                    "swarm_codec_encode", "swarm_codec_decode", "swarm_status_string",
+                    "swarm_stage_coded_workspace_bytes", "swarm_stage_forward_coded", "swarm_stage_backward_coded")
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
@@ -79,6 +80,14 @@ def load_library():
     lib.swarm_codec_decode.restype = C.c_int
     lib.swarm_codec_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_int32,
                                        C.c_void_p]
+    lib.swarm_stage_coded_workspace_bytes.restype = C.c_size_t
+    lib.swarm_stage_coded_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int]
+    lib.swarm_stage_forward_coded.restype = C.c_int
+    lib.swarm_stage_forward_coded.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs)] + [C.c_void_p] * 6 + \
+                                             [C.c_size_t, C.c_void_p]
+    lib.swarm_stage_backward_coded.restype = C.c_int
+    lib.swarm_stage_backward_coded.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs)] + [C.c_void_p] * 5 + \
+                                              [C.POINTER(_BlockPtrs), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -167,3 +176,29 @@ def swarm_codec_decode(codes: torch.Tensor, scales: torch.Tensor, tensor: torch.
                                            _dtype_code(tensor), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_codec_decode")
+
+
+def swarm_stage_coded_workspace_bytes(cfg: StageConfig, for_backward: bool) -> int:
+    return int(load_library().swarm_stage_coded_workspace_bytes(C.byref(cfg.c), 1 if for_backward else 0))
+
+
+def swarm_stage_forward_coded(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_codes: torch.Tensor,
+                              x_scales: torch.Tensor, x_dec: torch.Tensor, y_codes: torch.Tensor,
+                              y_scales: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    st = load_library().swarm_stage_forward_coded(C.byref(cfg.c), _block_array(params), _ptr(x_codes), _ptr(x_scales),
+                                                  _ptr(x_dec), _ptr(y_codes), _ptr(y_scales), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_stage_forward_coded")
+
+
+def swarm_stage_backward_coded(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_in: torch.Tensor,
+                               g_codes: torch.Tensor, g_scales: torch.Tensor, gin_codes: torch.Tensor,
+                               gin_scales: torch.Tensor, grad_params: List[Dict[str, torch.Tensor]],
+                               workspace: torch.Tensor, stream=None) -> None:
+    st = load_library().swarm_stage_backward_coded(C.byref(cfg.c), _block_array(params), _ptr(x_in), _ptr(g_codes),
+                                                   _ptr(g_scales), _ptr(gin_codes), _ptr(gin_scales),
+                                                   _block_array(grad_params), _ptr(workspace),
+                                                   workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_stage_backward_coded")

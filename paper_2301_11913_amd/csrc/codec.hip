@@ -10,7 +10,7 @@
 // butterfly inside the octet.  A wavefront covers 512 contiguous elements:
 // loads are 16 B (bf16) or 2 x 16 B (fp32) per lane, code stores 8 B per lane,
 // all fully coalesced.  HBM-bound: 3.0625 B/element from bf16, 5.0625 from fp32.
-#include "common.h"
+#include "kernels.h"
 
 namespace swarm {
 
@@ -137,6 +137,32 @@ static int codec_grid(size_t n_elems) {
   return (int)(blocks < cap ? (blocks ? blocks : 1) : cap);
 }
 
+swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, float* scales, bool bf16,
+                                 hipStream_t st) {
+  if (n == 0) return SWARM_OK;
+  const int grid = codec_grid(n);
+  if (bf16)
+    hipLaunchKernelGGL(codec_encode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, (const bf16_raw*)tensor, n,
+                       codes, scales);
+  else
+    hipLaunchKernelGGL(codec_encode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, (const float*)tensor, n, codes,
+                       scales);
+  return launch_status();
+}
+
+swarm_status codec_decode_launch(const int8_t* codes, const float* scales, size_t n, void* tensor, bool bf16,
+                                 hipStream_t st) {
+  if (n == 0) return SWARM_OK;
+  const int grid = codec_grid(n);
+  if (bf16)
+    hipLaunchKernelGGL(codec_decode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n,
+                       (bf16_raw*)tensor);
+  else
+    hipLaunchKernelGGL(codec_decode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n,
+                       (float*)tensor);
+  return launch_status();
+}
+
 }  // namespace swarm
 
 using namespace swarm;
@@ -148,15 +174,7 @@ extern "C" swarm_status swarm_codec_encode(const void* tensor, int32_t dtype, si
   if (n_elems == 0) return SWARM_OK;
   if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
   if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 3)) return SWARM_ERR_SHAPE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  int grid = codec_grid(n_elems);
-  if (dtype == SWARM_BF16)
-    hipLaunchKernelGGL(codec_encode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st,
-                       (const bf16_raw*)tensor, n_elems, codes, scales);
-  else
-    hipLaunchKernelGGL(codec_encode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, (const float*)tensor,
-                       n_elems, codes, scales);
-  return launch_status();
+  return codec_encode_launch(tensor, n_elems, codes, scales, dtype == SWARM_BF16, (hipStream_t)hip_stream);
 }
 
 extern "C" swarm_status swarm_codec_decode(const int8_t* codes, const float* scales, size_t n_elems, int32_t block,
@@ -166,13 +184,5 @@ extern "C" swarm_status swarm_codec_decode(const int8_t* codes, const float* sca
   if (n_elems == 0) return SWARM_OK;
   if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
   if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 3)) return SWARM_ERR_SHAPE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  int grid = codec_grid(n_elems);
-  if (dtype == SWARM_BF16)
-    hipLaunchKernelGGL(codec_decode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n_elems,
-                       (bf16_raw*)tensor);
-  else
-    hipLaunchKernelGGL(codec_decode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n_elems,
-                       (float*)tensor);
-  return launch_status();
+  return codec_decode_launch(codes, scales, n_elems, tensor, dtype == SWARM_BF16, (hipStream_t)hip_stream);
 }

@@ -18,6 +18,7 @@ constexpr int kLnRowsPerBlock = 16;          // backward: rows per workgroup
 template <typename T> struct V8;
 template <> struct V8<bf16_raw> {
   struct Raw { uint4 v; };                   // 8 elements as loaded (keeps register use low)
+  static __device__ __forceinline__ float rounded(float x) { return bf16_bits_to_float(float_to_bf16_bits(x)); }
   static __device__ __forceinline__ Raw load_raw(const bf16_raw* p) { return Raw{*reinterpret_cast<const uint4*>(p)}; }
   static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
     const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
@@ -45,6 +46,7 @@ template <> struct V8<bf16_raw> {
 };
 template <> struct V8<float> {
   struct Raw { float4 a, b; };
+  static __device__ __forceinline__ float rounded(float x) { return x; }
   static __device__ __forceinline__ Raw load_raw(const float* p) {
     return Raw{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
   }
@@ -63,11 +65,16 @@ template <> struct V8<float> {
 };
 
 // NIT = chunks per lane held in registers (d <= NIT * 512).
-template <typename T, int NIT>
+// DEC: the input row arrives as int8 codes + one fp32 scale per 64 elements (stage-boundary codec); the
+// decoded row (code * scale rounded to T, exactly what the stand-alone decode kernel writes) is stored to
+// xdec and normalised.
+template <typename T, int NIT, bool DEC>
 __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                             const T* __restrict__ beta, T* __restrict__ y,
                                                             float* __restrict__ mean, float* __restrict__ rstd,
-                                                            int rows, int d, float eps) {
+                                                            int rows, int d, float eps,
+                                                            const int8_t* __restrict__ codes,
+                                                            const float* __restrict__ scales, T* __restrict__ xdec) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nchunk = d >> 3;
@@ -80,7 +87,20 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
     for (int it = 0; it < NIT; ++it) {
       const int c = lane + it * 64;
       if (c < nchunk) {
-        V8<T>::load(xr + c * 8, v[it]);
+        if constexpr (DEC) {
+          const size_t e0 = (size_t)row * d + (size_t)c * 8;
+          const uint2 cw = *reinterpret_cast<const uint2*>(codes + e0);
+          const float sc = scales[e0 >> 6];
+          const uint32_t w[2] = {cw.x, cw.y};
+          float t[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) t[i] = (float)(int)(int8_t)((w[i >> 2] >> (8 * (i & 3))) & 0xFF) * sc;
+          V8<T>::store(xdec + e0, t);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[it][i] = V8<T>::rounded(t[i]);   // the values just stored
+        } else {
+          V8<T>::load(xr + c * 8, v[it]);
+        }
 #pragma unroll
         for (int i = 0; i < 8; ++i) s += v[it][i];
       }
@@ -118,14 +138,18 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
 // carries only d/256 dgamma / dbeta partial sums; the two row statistics are combined across the
 // wavefronts through LDS, four rows per barrier.  A workgroup walks kLnRowsPerBlock rows and writes its
 // column partials to partial[gridDim.x][2][d] (dgamma then dbeta); a fixed-order second stage adds them up.
+// ENC: dx leaves int8-encoded (stage-boundary codec): a lane octet holds one 64-element block of the
+// row (needs d % 256 == 0 so that blocks do not straddle wavefronts); the values are rounded to T first,
+// so codes and scales equal those of the stand-alone encode kernel on the stored dx.
 constexpr int kLnBatch = 4;                  // rows per barrier
-template <typename T, int NITQ>
+template <typename T, int NITQ, bool ENC>
 __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                             const float* __restrict__ mean,
                                                             const float* __restrict__ rstd,
                                                             const T* __restrict__ gamma, const T* __restrict__ dres,
                                                             T* __restrict__ dx, float* __restrict__ partial, int rows,
-                                                            int d) {
+                                                            int d, int8_t* __restrict__ codes,
+                                                            float* __restrict__ scales) {
   __shared__ float red[2][kLnBatch][kLnWaves][2];
   typedef typename V8<T>::Raw Raw;
   const int lane = threadIdx.x & 63;
@@ -198,7 +222,28 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
           V8<T>::unpack(graw[it], g);
 #pragma unroll
           for (int i = 0; i < 8; ++i) o[i] = res[i] + rs[r] * (dv[i] * g[i] - m1 - (xv[i] - mu[r]) * rs[r] * m2);
-          V8<T>::store(dx + (size_t)row * d + (size_t)(cbase + c) * 8, o);
+          if constexpr (ENC) {
+            const size_t e0 = (size_t)row * d + (size_t)(cbase + c) * 8;
+            float amax = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { o[i] = V8<T>::rounded(o[i]); amax = fmaxf(amax, fabsf(o[i])); }
+            amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+            amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+            amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+            const float sc = amax / 127.0f;
+            uint32_t w[2] = {0u, 0u};
+            if (sc != 0.0f) {
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                const float q = fminf(fmaxf(rintf(o[i] / sc), -127.0f), 127.0f);
+                w[i >> 2] |= ((uint32_t)(int)q & 0xFFu) << (8 * (i & 3));
+              }
+            }
+            *reinterpret_cast<uint2*>(codes + e0) = make_uint2(w[0], w[1]);
+            if ((lane & 7) == 0) scales[e0 >> 6] = sc;
+          } else {
+            V8<T>::store(dx + (size_t)row * d + (size_t)(cbase + c) * 8, o);
+          }
         }
       }
     }
@@ -275,13 +320,13 @@ __global__ __launch_bounds__(256) void reduce_rows_accum_kernel(const float* __r
   }
 }
 
-template <typename T>
+template <typename T, bool DEC>
 swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows, int d,
-                             float eps, hipStream_t st) {
+                             float eps, const int8_t* codes, const float* scales, T* xdec, hipStream_t st) {
   const int grid = std::min((rows + kLnWaves - 1) / kLnWaves, 256 * 8);
-#define LN_FWD(NIT)                                                                                         \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, NIT>), dim3(grid), dim3(kLnThreads), 0, st, x, g, b, y, mean, rstd, \
-                     rows, d, eps)
+#define LN_FWD(NIT)                                                                                              \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, NIT, DEC>), dim3(grid), dim3(kLnThreads), 0, st, x, g, b, y, mean, rstd, \
+                     rows, d, eps, codes, scales, xdec)
   if (d <= 512) LN_FWD(1);
   else if (d <= 1024) LN_FWD(2);
   else if (d <= 2048) LN_FWD(4);
@@ -292,13 +337,14 @@ swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* me
   return launch_status();
 }
 
-template <typename T>
+template <typename T, bool ENC>
 swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const float* rstd, const T* g,
-                             const T* dres, T* dx, float* partial, int rows, int d, hipStream_t st) {
+                             const T* dres, T* dx, float* partial, int rows, int d, int8_t* codes, float* scales,
+                             hipStream_t st) {
   const int grid = (rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
-#define LN_BWD(NITQ)                                                                                        \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
-                     dres, dx, partial, rows, d)
+#define LN_BWD(NITQ)                                                                                             \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ, ENC>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
+                     dres, dx, partial, rows, d, codes, scales)
   if (d <= 2048) LN_BWD(1);
   else if (d <= 4096) LN_BWD(2);
   else if (d <= 8192) LN_BWD(4);
@@ -312,26 +358,43 @@ swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const f
 swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
                            int T, int d, float eps, bool bf16, hipStream_t st) {
   if (bf16)
-    return ln_fwd_dispatch<bf16_raw>((const bf16_raw*)x, (const bf16_raw*)gamma, (const bf16_raw*)beta,
-                                     (bf16_raw*)y, mean, rstd, T, d, eps, st);
-  return ln_fwd_dispatch<float>((const float*)x, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd,
-                                T, d, eps, st);
+    return ln_fwd_dispatch<bf16_raw, false>((const bf16_raw*)x, (const bf16_raw*)gamma, (const bf16_raw*)beta,
+                                            (bf16_raw*)y, mean, rstd, T, d, eps, nullptr, nullptr, nullptr, st);
+  return ln_fwd_dispatch<float, false>((const float*)x, (const float*)gamma, (const float*)beta, (float*)y, mean,
+                                       rstd, T, d, eps, nullptr, nullptr, nullptr, st);
+}
+
+swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void* xdec, const void* gamma,
+                                  const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
+                                  bool bf16, hipStream_t st) {
+  if (bf16)
+    return ln_fwd_dispatch<bf16_raw, true>(nullptr, (const bf16_raw*)gamma, (const bf16_raw*)beta, (bf16_raw*)y,
+                                           mean, rstd, T, d, eps, codes, scales, (bf16_raw*)xdec, st);
+  return ln_fwd_dispatch<float, true>(nullptr, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, T, d,
+                                      eps, codes, scales, (float*)xdec, st);
 }
 
 size_t layernorm_bwd_scratch_floats(int T, int d) {
   return (size_t)((T + kLnRowsPerBlock - 1) / kLnRowsPerBlock) * 2 * d;
 }
 
+// codes != nullptr: dx is not written; its int8 encoding goes to codes / scales (needs d % 256 == 0)
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
-                           bool bf16, hipStream_t st) {
+                           bool bf16, hipStream_t st, int8_t* codes, float* scales) {
   swarm_status s;
-  if (bf16)
-    s = ln_bwd_dispatch<bf16_raw>((const bf16_raw*)dy, (const bf16_raw*)x, mean, rstd, (const bf16_raw*)gamma,
-                                  (const bf16_raw*)dres, (bf16_raw*)dx, partial, T, d, st);
-  else
-    s = ln_bwd_dispatch<float>((const float*)dy, (const float*)x, mean, rstd, (const float*)gamma,
-                               (const float*)dres, (float*)dx, partial, T, d, st);
+  if (codes && (d % 256)) return SWARM_ERR_SHAPE;
+  if (bf16) {
+    const bf16_raw *a = (const bf16_raw*)dy, *b = (const bf16_raw*)x, *g = (const bf16_raw*)gamma,
+                   *r = (const bf16_raw*)dres;
+    s = codes ? ln_bwd_dispatch<bf16_raw, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st)
+              : ln_bwd_dispatch<bf16_raw, false>(a, b, mean, rstd, g, r, (bf16_raw*)dx, partial, T, d, nullptr, nullptr,
+                                                 st);
+  } else {
+    const float *a = (const float*)dy, *b = (const float*)x, *g = (const float*)gamma, *r = (const float*)dres;
+    s = codes ? ln_bwd_dispatch<float, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st)
+              : ln_bwd_dispatch<float, false>(a, b, mean, rstd, g, r, (float*)dx, partial, T, d, nullptr, nullptr, st);
+  }
   if (s != SWARM_OK) return s;
   const int P = (T + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
   const int grid = (d + 63) / 64;

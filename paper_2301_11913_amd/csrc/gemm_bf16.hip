@@ -242,6 +242,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   if (g.epilogue != EPI_ACCUM_F32)   // the bf16 epilogue moves 8-element chunks
     vec_ok = vec_ok && g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.bias || al16(g.bias)) &&
              (!g.aux || (al16(g.aux) && g.ldaux % 8 == 0)) && (!g.C2 || (al16(g.C2) && g.ldc2 % 8 == 0));
+  if (g.epilogue == EPI_BIAS_RESID_ENCODE && (!vec_ok || g.N % 64 || g.ldc != g.N || !g.scales)) return SWARM_ERR_SHAPE;
   if (!vec_ok || (g.a_trans && !g.b_trans)) return gemm_generic(g, true, st);
   static const bool use_dma = std::getenv("SWARM_GEMM_NO_DMA") == nullptr;
   if (use_dma) {
@@ -252,7 +253,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
-  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;
+  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= 160) {
     k.tiles_m = (g.M + 255) / 256; k.tiles_n = (g.N + 255) / 256;

@@ -18,6 +18,7 @@ struct KArgs {
   int epilogue;
   const bf16_raw* bias; const bf16_raw* aux; int ldaux;
   bf16_raw* C2; int ldc2;
+  float* scales;   // EPI_BIAS_RESID_ENCODE
   int tiles_m, tiles_n;
   int group_m;   // tile rows walked together (L2 reuse of the B panel)
 };
@@ -108,7 +109,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
   float bias[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) bias[e] = 0.f;
-  if (col_ok && (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU))
+  if (col_ok && (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RESID_ENCODE))
     unpack8(*reinterpret_cast<const uint4*>(p.bias + col), bias);
   bf16_raw* C = reinterpret_cast<bf16_raw*>(p.C);
 #pragma unroll
@@ -124,8 +125,36 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
       const int row = row0 + i * 32 + rl;
       const float4 v0 = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 8 * c8);
       const float4 v1 = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 8 * c8 + 4);
-      if (!col_ok || (GUARD && row >= p.M)) continue;
+      if (!col_ok || (GUARD && row >= p.M)) continue;     // uniform over a lane octet (N % 64 == 0 when encoding)
       float x[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      if (epi == EPI_BIAS_RESID_ENCODE) {
+        // stage-exit codec fused: the 8 lanes of a row segment hold one 64-element block.  Values are
+        // rounded to bf16 first, so codes and scales equal the stand-alone encode of the stored tensor.
+        float a[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          x[e] = bf16_bits_to_float(float_to_bf16_bits(x[e] + bias[e] + a[e]));
+          amax = fmaxf(amax, fabsf(x[e]));
+        }
+        amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+        const float sc = amax / 127.0f;
+        uint32_t w[2] = {0u, 0u};
+        if (sc != 0.0f) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float q = fminf(fmaxf(rintf(x[e] / sc), -127.0f), 127.0f);
+            w[e >> 2] |= ((uint32_t)(int)q & 0xFFu) << (8 * (e & 3));
+          }
+        }
+        const size_t e0 = (size_t)row * p.ldc + col;
+        *reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(p.C) + e0) = make_uint2(w[0], w[1]);
+        if (c8 == 0) p.scales[e0 >> 6] = sc;
+        continue;
+      }
       if (epi == EPI_BIAS) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] += bias[e];

@@ -217,7 +217,7 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
-  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2;
+  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {
     k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
     return launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);

@@ -18,7 +18,8 @@ enum GemmEpilogue {
   EPI_BIAS_RESID = 2,  // C = acc + bias[n] + aux[m,n]
   EPI_BIAS_GELU = 3,   // u = acc + bias[n]; C = gelu(u); C2 = u when C2 != nullptr
   EPI_DGELU = 4,       // C = acc * gelu'(aux[m,n])
-  EPI_ACCUM_F32 = 5    // C (fp32) += acc
+  EPI_ACCUM_F32 = 5,   // C (fp32) += acc
+  EPI_BIAS_RESID_ENCODE = 6   // x = acc + bias[n] + aux[m,n] rounded to bf16, stored int8-encoded: C = codes, scales
 };
 
 struct GemmArgs {
@@ -30,6 +31,7 @@ struct GemmArgs {
   const void* bias;        // [N], activation dtype
   const void* aux; int ldaux;   // [M,N] residual or pre-activation, activation dtype
   void* C2; int ldc2;      // optional second output (pre-activation u)
+  float* scales;           // EPI_BIAS_RESID_ENCODE: one fp32 scale per 64 consecutive elements of C (ldc == N)
 };
 
 // T = float: plain FMA tiles (parity configuration); T = bf16: MFMA kernel.
@@ -45,9 +47,19 @@ swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, v
 // dx = dres + LN-backward(dy), dgamma += sum_t dy*xhat, dbeta += sum_t dy.
 // `partial` is scratch of layernorm_bwd_scratch_floats(T, d) floats.
 size_t layernorm_bwd_scratch_floats(int T, int d);
+// With codes != nullptr dx is not stored: its int8 blockwise encoding is (fused stage-exit encode, d % 256 == 0).
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
-                           bool bf16, hipStream_t st);
+                           bool bf16, hipStream_t st, int8_t* codes = nullptr, float* scales = nullptr);
+// LayerNorm of a row that arrives int8-encoded: xdec receives the decoded row (fused stage-entry decode).
+swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void* xdec, const void* gamma,
+                                  const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
+                                  bool bf16, hipStream_t st);
+// Stand-alone codec launches (same kernels as the C ABI entry points).
+swarm_status codec_decode_launch(const int8_t* codes, const float* scales, size_t n, void* tensor, bool bf16,
+                                 hipStream_t st);
+swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, float* scales, bool bf16,
+                                 hipStream_t st);
 // out[n] += sum_t X[t,n]  (X [T,N] in the activation dtype, out fp32); scratch of colsum_scratch_floats floats.
 size_t colsum_scratch_floats(int T, int N);
 swarm_status colsum_accum(const void* X, int T, int N, float* out, float* partial, bool bf16, hipStream_t st);

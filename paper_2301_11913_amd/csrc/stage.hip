@@ -84,11 +84,22 @@ swarm_status gemm(const Dims& D, const GemmArgs& g, hipStream_t st) {
     if (_s != SWARM_OK) return _s;      \
   } while (0)
 
+// Stage-boundary codec fused into a block: `in_codes` -> the block input arrives int8-encoded and is decoded
+// into s.x by LN1; `out_codes` -> the block output leaves int8-encoded from the FFN2 epilogue.
+struct Boundary {
+  const int8_t* in_codes = nullptr; const float* in_scales = nullptr;
+  int8_t* out_codes = nullptr; float* out_scales = nullptr;
+};
+
 // y = block(x): writes every intermediate into `s`; the last GEMM is skipped when y == nullptr.
 swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Saved& s, void* y, float eps,
-                           hipStream_t st) {
+                           hipStream_t st, const Boundary& bd = Boundary()) {
   const int T = D.T, d = D.d, f = D.f;
-  SWARM_TRY(layernorm_fwd(s.x, p.ln1_g, p.ln1_b, s.a, s.mean1, s.rstd1, T, d, eps, D.bf16, st));
+  if (bd.in_codes)
+    SWARM_TRY(layernorm_fwd_decode(bd.in_codes, bd.in_scales, const_cast<void*>(s.x), p.ln1_g, p.ln1_b, s.a, s.mean1,
+                                   s.rstd1, T, d, eps, D.bf16, st));
+  else
+    SWARM_TRY(layernorm_fwd(s.x, p.ln1_g, p.ln1_b, s.a, s.mean1, s.rstd1, T, d, eps, D.bf16, st));
   GemmArgs q{};
   q.M = T; q.N = 3 * d; q.K = d; q.A = s.a; q.lda = d; q.B = p.w_qkv; q.ldb = d; q.C = s.qkv; q.ldc = 3 * d;
   q.epilogue = EPI_BIAS; q.bias = p.b_qkv;
@@ -103,10 +114,11 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   f1.M = T; f1.N = f; f1.K = d; f1.A = s.c; f1.lda = d; f1.B = p.w_1; f1.ldb = d; f1.C = s.g; f1.ldc = f;
   f1.epilogue = EPI_BIAS_GELU; f1.bias = p.b_1; f1.C2 = s.u; f1.ldc2 = f;
   SWARM_TRY(gemm(D, f1, st));
-  if (y) {
+  if (y || bd.out_codes) {
     GemmArgs f2{};
     f2.M = T; f2.N = d; f2.K = f; f2.A = s.g; f2.lda = f; f2.B = p.w_2; f2.ldb = f; f2.C = y; f2.ldc = d;
     f2.epilogue = EPI_BIAS_RESID; f2.bias = p.b_2; f2.aux = s.h; f2.ldaux = d;
+    if (bd.out_codes) { f2.epilogue = EPI_BIAS_RESID_ENCODE; f2.C = bd.out_codes; f2.scales = bd.out_scales; }
     SWARM_TRY(gemm(D, f2, st));
   }
   return SWARM_OK;
@@ -137,7 +149,8 @@ swarm_status data_grad(const Dims& D, const void* dY, int n_out, const void* W, 
 }
 
 swarm_status block_backward(const Dims& D, const swarm_block_params& p, const swarm_block_grads& gp, const Saved& s,
-                            const BwdTemps& t, const void* dy, void* dx, hipStream_t st) {
+                            const BwdTemps& t, const void* dy, void* dx, hipStream_t st, int8_t* dx_codes = nullptr,
+                            float* dx_scales = nullptr) {
   const int d = D.d, f = D.f;
   // y = h + gelu(u) W2^T + b2
   SWARM_TRY(weight_grads(D, dy, d, s.g, f, gp.w_2, gp.b_2, t.partial, st));
@@ -157,7 +170,7 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
   SWARM_TRY(data_grad(D, t.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
   // a = LN1(x);  dx = dh + LN1'(da)
   SWARM_TRY(layernorm_bwd(t.da, s.x, s.mean1, s.rstd1, p.ln1_g, t.dh, dx, gp.ln1_g, gp.ln1_b, t.partial, D.T, d,
-                          D.bf16, st));
+                          D.bf16, st, dx_codes, dx_scales));
   return SWARM_OK;
 }
 
@@ -289,6 +302,114 @@ extern "C" swarm_status swarm_stage_backward(const swarm_stage_config* cfg, cons
       void* dx = (app == 0) ? grad_in : P.dz[app & 1];
       SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, dx, st));
       dy = dx;
+    }
+  return SWARM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Entry points with the boundary codec fused into the stage.  Fused kernels are used for bf16 with
+// d_model % 256 == 0; otherwise the same results come from the stand-alone codec kernels around the stage.
+namespace swarm {
+namespace {
+bool fuse_codec(const Dims& D) { return D.bf16 && D.d % 256 == 0; }
+}  // namespace
+}  // namespace swarm
+
+extern "C" size_t swarm_stage_coded_workspace_bytes(const swarm_stage_config* cfg, int for_backward) {
+  const size_t base = swarm_stage_workspace_bytes(cfg, for_backward);
+  if (!base) return 0;
+  const Dims D = dims_of(cfg);
+  return base + 256 + 2 * (((size_t)D.T * D.d * D.es + 255) & ~(size_t)255);   // two boundary tensors of scratch
+}
+
+extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                  const int8_t* x_codes, const float* x_scales, void* x_dec,
+                                                  int8_t* y_codes, float* y_scales, void* workspace,
+                                                  size_t workspace_bytes, void* hip_stream) {
+  if (!cfg || !params || !x_codes || !x_scales || !x_dec || !y_codes || !y_scales || !workspace) return SWARM_ERR_NULL;
+  if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
+  if (!params_ok(params, cfg->n_layers)) return SWARM_ERR_NULL;
+  if (!aligned16(x_dec) || !aligned16(x_codes) || !aligned16(y_codes) || ((uintptr_t)workspace & 255))
+    return SWARM_ERR_SHAPE;
+  if (swarm_stage_coded_workspace_bytes(cfg, 0) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  const Dims D = dims_of(cfg);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t base = swarm_stage_workspace_bytes(cfg, 0);
+  void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
+  const size_t n = (size_t)D.T * D.d;
+  if (!fuse_codec(D)) {
+    SWARM_TRY(codec_decode_launch(x_codes, x_scales, n, x_dec, D.bf16, st));
+    SWARM_TRY(swarm_stage_forward(cfg, params, x_dec, tmp, workspace, base, hip_stream));
+    return codec_encode_launch(tmp, n, y_codes, y_scales, D.bf16, st);
+  }
+  FwdPlan P;
+  plan_forward(D, workspace, P);
+  const void* cur = x_dec;
+  int app = 0;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
+      const bool last = app == D.apps - 1;
+      Boundary bd;
+      if (app == 0) { bd.in_codes = x_codes; bd.in_scales = x_scales; }
+      if (last) { bd.out_codes = y_codes; bd.out_scales = y_scales; }
+      void* y = last ? nullptr : P.z[app & 1];
+      P.s.x = cur;
+      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st, bd));
+      cur = y;
+    }
+  return SWARM_OK;
+}
+
+extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                   const void* x_in, const int8_t* g_codes, const float* g_scales,
+                                                   int8_t* gin_codes, float* gin_scales,
+                                                   const swarm_block_grads* grad_params, void* workspace,
+                                                   size_t workspace_bytes, void* hip_stream) {
+  if (!cfg || !params || !x_in || !g_codes || !g_scales || !gin_codes || !gin_scales || !grad_params || !workspace)
+    return SWARM_ERR_NULL;
+  if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
+  if (!params_ok(params, cfg->n_layers) || !params_ok((const swarm_block_params*)grad_params, cfg->n_layers))
+    return SWARM_ERR_NULL;
+  if (!aligned16(x_in) || !aligned16(g_codes) || !aligned16(gin_codes) || ((uintptr_t)workspace & 255))
+    return SWARM_ERR_SHAPE;
+  if (swarm_stage_coded_workspace_bytes(cfg, 1) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  const Dims D = dims_of(cfg);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t base = swarm_stage_workspace_bytes(cfg, 1);
+  void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
+  const size_t n = (size_t)D.T * D.d;
+  // the output gradient has several readers (bias sums, two GEMMs, LayerNorm backward): decode it once
+  SWARM_TRY(codec_decode_launch(g_codes, g_scales, n, tmp, D.bf16, st));
+  if (!fuse_codec(D)) {
+    void* gin = (char*)tmp + (((size_t)D.T * D.d * D.es + 255) & ~(size_t)255);
+    SWARM_TRY(swarm_stage_backward(cfg, params, x_in, tmp, gin, grad_params, workspace, base, hip_stream));
+    return codec_encode_launch(gin, n, gin_codes, gin_scales, D.bf16, st);
+  }
+  BwdPlan P;
+  plan_backward(D, workspace, P);
+  const void* cur = x_in;
+  int app = 0;
+  for (int l = 0; l < cfg->n_layers; ++l)
+    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
+      P.saved[app].x = cur;
+      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];
+      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
+      cur = y;
+    }
+  const void* dy = tmp;
+  app = D.apps - 1;
+  for (int l = cfg->n_layers - 1; l >= 0; --l)
+    for (int r = cfg->n_repeat - 1; r >= 0; --r, --app) {
+      if (app == 0) {
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, nullptr, st, gin_codes,
+                                 gin_scales));
+      } else {
+        void* dx = P.dz[app & 1];
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, dx, st));
+        dy = dx;
+      }
     }
   return SWARM_OK;
 }
