@@ -23,6 +23,15 @@ biased variance, scores scaled by 1/sqrt(d_head).  For a token row x:
     c = LN(h; g2, b2)                     u = c W1^T + b1,   g = gelu(u)
     y = h + g W2^T + b2
 
+Second block kind, "rotary_geglu" (appendix "Additional Details for Section 4.3": the large-scale model is
+the standard Transformer with two changes, rotary position embeddings and GeGLU activations; the paper
+gives no formulas, so the cited definitions are used):
+  * rotary: in every head, q and k are rotated pairwise, (x_{2i}, x_{2i+1}) by the angle
+    pos * 10000^(-2i/d_head), pos = position in the sequence (RoFormer's interleaved form, full head width);
+  * GeGLU: u = c W1^T + b1 with W1 [2f, d]; g = gelu(u[:, :f]) * u[:, f:]; y = h + g W2^T + b2 (W2 [d, f]).
+Everything else is unchanged.  Pins: finite differences, a PyTorch autograd re-statement, the rotary
+relative-position property, and the 1.01 B parameter count of the Section 4.3 model.
+
 Plain numpy; np.matmul is the only library primitive; the arithmetic dtype is
 the `dt` argument (float64 for the pins and most parity tests, float32 where
 the size demands it).  No blocking, fusion or reordering.
@@ -76,6 +85,23 @@ def gelu_grad(u):
     return cdf + u * pdf
 
 
+def rotary_angles(S, dh, dt):
+    """cos, sin [S, dh/2] of pos * 10000^(-2i/dh)."""
+    inv = 10000.0 ** (-np.arange(0, dh, 2, dtype=np.float64) / dh)
+    ang = np.arange(S, dtype=np.float64)[:, None] * inv[None, :]
+    return np.cos(ang).astype(dt), np.sin(ang).astype(dt)
+
+
+def rotary(t, cos, sin, inverse=False):
+    """t [B,H,S,dh]: rotate the pairs (t[..., 2i], t[..., 2i+1]); inverse = rotation by the negative angle."""
+    te, to = t[..., 0::2], t[..., 1::2]
+    s = -sin if inverse else sin
+    out = np.empty_like(t)
+    out[..., 0::2] = te * cos - to * s
+    out[..., 1::2] = te * s + to * cos
+    return out
+
+
 def _split_heads(t, B, S, H, dh):
     return t.reshape(B, S, H, dh).transpose(0, 2, 1, 3)      # [B,H,S,dh]
 
@@ -109,7 +135,7 @@ def attention_bwd(do, q, k, v, p):
 
 
 # ----------------------------------------------------------------- block
-def block_forward(x, p, n_heads, eps, B, S):
+def block_forward(x, p, n_heads, eps, B, S, kind="gelu"):
     """x [T,d] -> (y [T,d], cache of intermediates)."""
     T, d = x.shape
     dh = d // n_heads
@@ -118,19 +144,27 @@ def block_forward(x, p, n_heads, eps, B, S):
     q = _split_heads(qkv[:, :d], B, S, n_heads, dh)
     k = _split_heads(qkv[:, d:2 * d], B, S, n_heads, dh)
     v = _split_heads(qkv[:, 2 * d:], B, S, n_heads, dh)
+    rope = None
+    if kind == "rotary_geglu":
+        rope = rotary_angles(S, dh, x.dtype)
+        q, k = rotary(q, *rope), rotary(k, *rope)
     o4, prob = attention_fwd(q, k, v)
     o = _merge_heads(o4, B, S, n_heads, dh)
     h = x + o @ p["w_o"].T + p["b_o"]
     c, xh2, r2 = layernorm_fwd(h, p["ln2_g"], p["ln2_b"], eps)
     u = c @ p["w_1"].T + p["b_1"]
-    g = gelu(u)
+    if kind == "rotary_geglu":
+        f = u.shape[1] // 2
+        g = gelu(u[:, :f]) * u[:, f:]
+    else:
+        g = gelu(u)
     y = h + g @ p["w_2"].T + p["b_2"]
     cache = dict(xh1=xh1, r1=r1, a=a, q=q, k=k, v=v, prob=prob, o=o,
-                 xh2=xh2, r2=r2, c=c, u=u, g=g)
+                 xh2=xh2, r2=r2, c=c, u=u, g=g, rope=rope)
     return y, cache
 
 
-def block_backward(dy, p, cache, grads, n_heads, B, S):
+def block_backward(dy, p, cache, grads, n_heads, B, S, kind="gelu"):
     """dy [T,d] -> dx [T,d]; parameter gradients are ADDED into `grads`."""
     T, d = dy.shape
     dh = d // n_heads
@@ -138,7 +172,12 @@ def block_backward(dy, p, cache, grads, n_heads, B, S):
     grads["w_2"] += dy.T @ cache["g"]
     grads["b_2"] += dy.sum(axis=0)
     dg = dy @ p["w_2"]
-    du = dg * gelu_grad(cache["u"])
+    if kind == "rotary_geglu":
+        u = cache["u"]
+        f = u.shape[1] // 2
+        du = np.concatenate([dg * u[:, f:] * gelu_grad(u[:, :f]), dg * gelu(u[:, :f])], axis=1)
+    else:
+        du = dg * gelu_grad(cache["u"])
     grads["w_1"] += du.T @ cache["c"]
     grads["b_1"] += du.sum(axis=0)
     dc = du @ p["w_1"]
@@ -152,6 +191,8 @@ def block_backward(dy, p, cache, grads, n_heads, B, S):
     do = dhid @ p["w_o"]
     do4 = _split_heads(do, B, S, n_heads, dh)
     dq, dk, dv = attention_bwd(do4, cache["q"], cache["k"], cache["v"], cache["prob"])
+    if kind == "rotary_geglu":          # q, k in the cache are the rotated ones; undo the rotation on their gradients
+        dq, dk = rotary(dq, *cache["rope"], inverse=True), rotary(dk, *cache["rope"], inverse=True)
     dqkv = np.concatenate([_merge_heads(dq, B, S, n_heads, dh),
                            _merge_heads(dk, B, S, n_heads, dh),
                            _merge_heads(dv, B, S, n_heads, dh)], axis=1)
@@ -173,7 +214,7 @@ def zero_grads(params, dt=np.float64):
     return [{k: np.zeros(np.shape(p[k]), dtype=dt) for k in PARAM_FIELDS} for p in params]
 
 
-def stage_forward(params, x_in, n_heads, n_repeat=1, eps=1e-5, dt=np.float64, keep=False):
+def stage_forward(params, x_in, n_heads, n_repeat=1, eps=1e-5, dt=np.float64, keep=False, kind="gelu"):
     """x_in [B,S,d] -> x_out [B,S,d]: each of the L parameter sets applied n_repeat times in a row."""
     B, S, d = x_in.shape
     P = cast_params(params, dt)
@@ -181,7 +222,7 @@ def stage_forward(params, x_in, n_heads, n_repeat=1, eps=1e-5, dt=np.float64, ke
     caches = []
     for p in P:
         for _ in range(n_repeat):
-            z, cache = block_forward(z, p, n_heads, eps, B, S)
+            z, cache = block_forward(z, p, n_heads, eps, B, S, kind)
             if keep:
                 caches.append(cache)
     out = z.reshape(B, S, d)
@@ -189,18 +230,18 @@ def stage_forward(params, x_in, n_heads, n_repeat=1, eps=1e-5, dt=np.float64, ke
 
 
 def stage_backward(params, x_in, grad_out, grad_params, n_heads, n_repeat=1, eps=1e-5,
-                   dt=np.float64):
+                   dt=np.float64, kind="gelu"):
     """Checkpointed backward: recompute the forward from x_in, then walk the L*R block
     applications in reverse.  Returns grad_in [B,S,d]; `grad_params` (list of L dicts)
     is accumulated into (+=), a shared set receiving the sum over its repeats."""
     B, S, d = x_in.shape
     P = cast_params(params, dt)
-    _, caches = stage_forward(params, x_in, n_heads, n_repeat, eps, dt, keep=True)
+    _, caches = stage_forward(params, x_in, n_heads, n_repeat, eps, dt, keep=True, kind=kind)
     dz = np.asarray(grad_out, dtype=dt).reshape(B * S, d)
     idx = len(caches)
     for l in reversed(range(len(P))):
         for _ in range(n_repeat):
             idx -= 1
-            dz = block_backward(dz, P[l], caches[idx], grad_params[l], n_heads, B, S)
+            dz = block_backward(dz, P[l], caches[idx], grad_params[l], n_heads, B, S, kind)
             caches[idx] = None
     return dz.reshape(B, S, d)

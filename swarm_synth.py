@@ -47,6 +47,7 @@ class Workload:
     ln_eps: float = 1e-5
     seed: int = BASE_SEED
     boundary_codec: bool = False   # stage entry/exit tensors travel as int8
+    block: str = "gelu"            # "gelu" | "rotary_geglu" (w_1, b_1 then have 2*d_ffn rows: gate | up)
 
     @property
     def tokens(self) -> int:
@@ -58,9 +59,10 @@ class Workload:
 
     def param_shapes(self) -> dict:
         d, f = self.d_model, self.d_ffn
+        f1 = 2 * f if self.block == "rotary_geglu" else f
         return {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (3 * d, d), "b_qkv": (3 * d,),
                 "w_o": (d, d), "b_o": (d,), "ln2_g": (d,), "ln2_b": (d,),
-                "w_1": (f, d), "b_1": (f,), "w_2": (d, f), "b_2": (d,)}
+                "w_1": (f1, d), "b_1": (f1,), "w_2": (d, f), "b_2": (d,)}
 
     def replace(self, **kw) -> "Workload":
         return dataclasses.replace(self, **kw)
@@ -87,6 +89,11 @@ WORKLOADS = {
     "e2e_bf16_d4096": _wl(5, "e2e_bf16_d4096", dtype="bf16", d_model=4096, n_heads=32, d_ffn=16384,
                           seq=2048, batch=4, n_layers=2, n_repeat=1, grad_sigma=1e-2,
                           boundary_codec=True),
+    # the Section 4.3 model's stage: one shared rotary + GeGLU block (d_model 4096) applied 16 times,
+    # sequences of up to 2048 tokens, one sequence per microbatch
+    "shared16_rope_geglu_d4096": _wl(6, "shared16_rope_geglu_d4096", dtype="bf16", d_model=4096, n_heads=32,
+                                     d_ffn=16384, seq=2048, batch=1, n_layers=1, n_repeat=16, grad_sigma=1e-2,
+                                     block="rotary_geglu", boundary_codec=True),
 }
 
 

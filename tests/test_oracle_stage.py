@@ -252,3 +252,121 @@ def test_table6_parameter_and_flop_counts():
         assert abs(weights - float(n_par)) / float(n_par) < 0.005
         model_flops = 6 * weights * 512 * int(layers)
         assert abs(model_flops - float(flops)) / float(flops) < 0.04
+
+
+# ------------------------------------------------------------------ rotary + GeGLU block
+def _tiny_rg(L=1, R=1):
+    wl = TINY.replace(n_layers=L, n_repeat=R, block="rotary_geglu", seed=71)
+    params = synth.make_params(wl)
+    for p in params:
+        for k in p:
+            if k[0] in "wb" or k.endswith("_b"):
+                p[k] = p[k] * 15.0
+    return wl, params, synth.make_x_in(wl), synth.make_grad_out(wl)
+
+
+@pytest.mark.parametrize("L,R", [(1, 1), (1, 3), (2, 1)])
+def test_rotary_geglu_finite_differences(L, R):
+    wl, params, x, G = _tiny_rg(L, R)
+    x, G = x.astype(np.float64), G.astype(np.float64)
+    params = osg.cast_params(params, np.float64)
+    kind = "rotary_geglu"
+    loss = lambda P, X: float((osg.stage_forward(P, X, wl.n_heads, R, wl.ln_eps, np.float64, kind=kind) * G).sum())
+    grads = osg.zero_grads(params)
+    gin = osg.stage_backward(params, x, G, grads, wl.n_heads, R, wl.ln_eps, kind=kind)
+    eps = 1e-6
+    fd = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        xp = x.copy(); xp[idx] += eps
+        xm = x.copy(); xm[idx] -= eps
+        fd[idx] = (loss(params, xp) - loss(params, xm)) / (2 * eps)
+    assert np.max(np.abs(fd - gin)) <= 1e-6 * max(1.0, np.max(np.abs(gin)))
+    rng = np.random.default_rng(2)
+    for l in range(L):
+        for k in osg.PARAM_FIELDS:
+            arr = params[l][k]
+            for f in rng.choice(arr.size, size=min(6, arr.size), replace=False):
+                idx = np.unravel_index(f, arr.shape)
+                old = arr[idx]
+                arr[idx] = old + eps; lp = loss(params, x)
+                arr[idx] = old - eps; lm = loss(params, x)
+                arr[idx] = old
+                assert abs((lp - lm) / (2 * eps) - grads[l][k][idx]) <= 2e-6 * max(1.0, np.max(np.abs(grads[l][k]))), (l, k)
+
+
+def test_rotary_geglu_against_torch_autograd():
+    """Independent re-statement with PyTorch ops (complex-number rotary, F.gelu, scaled_dot_product-free
+    attention) and autograd, fp64."""
+    wl = TINY.replace(d_model=64, n_heads=4, d_ffn=96, seq=19, batch=2, n_layers=1, n_repeat=2,
+                      block="rotary_geglu", seed=5)
+    params, x, G = synth.make_params(wl), synth.make_x_in(wl), synth.make_grad_out(wl)
+    for k in params[0]:
+        if k[0] in "wb":
+            params[0][k] = params[0][k] * 6.0
+    P = {k: torch.tensor(np.asarray(v, dtype=np.float64), requires_grad=True) for k, v in params[0].items()}
+    xt = torch.tensor(x.astype(np.float64), requires_grad=True)
+    B, S, d, H = wl.batch, wl.seq, wl.d_model, wl.n_heads
+    dh, f = d // H, wl.d_ffn
+    pos = torch.arange(S, dtype=torch.float64)
+    inv = 10000.0 ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+    rot = torch.polar(torch.ones(S, dh // 2, dtype=torch.float64), pos[:, None] * inv[None, :])   # e^{i angle}
+
+    def rope(t):                                   # t [B,H,S,dh]
+        tc = torch.view_as_complex(t.reshape(B, H, S, dh // 2, 2).contiguous())
+        return torch.view_as_real(tc * rot).reshape(B, H, S, dh)
+
+    z = xt
+    for _ in range(wl.n_repeat):
+        a = torch.nn.functional.layer_norm(z, (d,), P["ln1_g"], P["ln1_b"], wl.ln_eps)
+        qkv = a @ P["w_qkv"].T + P["b_qkv"]
+        q, k, v = (t.reshape(B, S, H, dh).transpose(1, 2) for t in qkv.split(d, dim=-1))
+        q, k = rope(q), rope(k)
+        s = q @ k.transpose(-1, -2) / math.sqrt(dh)
+        s = s.masked_fill(torch.triu(torch.ones(S, S, dtype=torch.bool), 1), float("-inf"))
+        o = (torch.softmax(s, -1) @ v).transpose(1, 2).reshape(B, S, d)
+        h = z + o @ P["w_o"].T + P["b_o"]
+        c = torch.nn.functional.layer_norm(h, (d,), P["ln2_g"], P["ln2_b"], wl.ln_eps)
+        u = c @ P["w_1"].T + P["b_1"]
+        g = torch.nn.functional.gelu(u[..., :f]) * u[..., f:]
+        z = h + g @ P["w_2"].T + P["b_2"]
+    z.backward(torch.tensor(G.astype(np.float64)))
+    kind = "rotary_geglu"
+    y = osg.stage_forward(params, x, H, wl.n_repeat, wl.ln_eps, np.float64, kind=kind)
+    grads = osg.zero_grads(params)
+    gin = osg.stage_backward(params, x, G, grads, H, wl.n_repeat, wl.ln_eps, kind=kind)
+    assert np.allclose(y, z.detach().numpy(), rtol=1e-10, atol=1e-10)
+    assert np.allclose(gin, xt.grad.numpy(), rtol=1e-9, atol=1e-11)
+    for k in osg.PARAM_FIELDS:
+        ref = P[k].grad.numpy()
+        assert np.allclose(grads[0][k], ref, rtol=1e-9, atol=1e-10 * max(1.0, np.abs(ref).max())), k
+
+
+def test_rotary_properties():
+    rng = np.random.default_rng(8)
+    S, dh = 11, 8
+    q = rng.standard_normal((1, 1, S, dh)); k = rng.standard_normal((1, 1, S, dh))
+    cos, sin = osg.rotary_angles(S, dh, np.float64)
+    rq, rk = osg.rotary(q, cos, sin), osg.rotary(k, cos, sin)
+    assert np.allclose(np.linalg.norm(rq, axis=-1), np.linalg.norm(q, axis=-1))        # rotations keep norms
+    assert np.array_equal(rq[0, 0, 0], q[0, 0, 0])                                       # position 0 is the identity
+    assert np.allclose(osg.rotary(rq, cos, sin, inverse=True), q, atol=1e-14)
+    # relative-position property: <R_i q, R_j k> depends on i - j only
+    q1 = np.broadcast_to(q[:, :, :1], q.shape); k1 = np.broadcast_to(k[:, :, :1], k.shape)
+    sc = osg.rotary(q1, cos, sin)[0, 0] @ osg.rotary(k1, cos, sin)[0, 0].T
+    for off in range(-3, 4):
+        dgl = np.diagonal(sc, off)
+        assert np.allclose(dgl, dgl[0], atol=1e-12)
+    # first pair rotates by exactly pos radians
+    assert np.allclose(cos[:, 0], np.cos(np.arange(S))) and np.allclose(sin[:, 0], np.sin(np.arange(S)))
+
+
+def test_section43_parameter_count():
+    row = [l.split() for l in open(os.path.join(HERE, "golden", "section43_model.txt")) if not l.startswith("#")][0]
+    total, stages, d, shared, vocab = float(row[0]), int(row[1]), int(row[2]), int(row[3]), int(row[4])
+    wl = synth.WORKLOADS["shared16_rope_geglu_d4096"]
+    assert wl.d_model == d and wl.n_repeat == shared and wl.n_layers == 1
+    shapes = wl.param_shapes()
+    per_stage = sum(int(np.prod(shapes[k])) for k in ("w_qkv", "w_o", "w_1", "w_2"))
+    assert per_stage == 4 * d * d + 3 * d * wl.d_ffn
+    model = stages * per_stage + vocab * d           # embedding shared with the LM head
+    assert abs(model - total) / total < 0.005
