@@ -36,7 +36,7 @@ def measured_traffic(workload):
 def model_flops(wl):
     """Paper convention (Table 6: 6 * parameters * tokens for fwd+bwd) plus the causal attention term."""
     T, d, f, S, B = wl.tokens, wl.d_model, wl.d_ffn, wl.seq, wl.batch
-    gemm = 2.0 * T * (4 * d * d + 2 * d * f)
+    gemm = 2.0 * T * (4 * d * d + (3 if wl.block == "rotary_geglu" else 2) * d * f)
     attn = 2.0 * B * wl.n_heads * wl.d_head * S * (S + 1)
     return 3.0 * (gemm + attn) * wl.n_layers * wl.n_repeat
 
@@ -57,9 +57,10 @@ def cpu_baseline(wl):
         x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(x.shape)
         cg, sg = ocodec.encode(G.reshape(-1))
         G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(G.shape)
-    y = osg.stage_forward(params, x, sample.n_heads, 1, sample.ln_eps, np.float64)
+    y = osg.stage_forward(params, x, sample.n_heads, 1, sample.ln_eps, np.float64, kind=sample.block)
     grads = osg.zero_grads(params, np.float64)
-    gin = osg.stage_backward(params, x, G, grads, sample.n_heads, 1, sample.ln_eps, np.float64)
+    gin = osg.stage_backward(params, x, G, grads, sample.n_heads, 1, sample.ln_eps, np.float64,
+                             kind=sample.block)
     if wl.boundary_codec:
         ocodec.encode(y.astype(np.float32).reshape(-1))
         ocodec.encode(gin.astype(np.float32).reshape(-1))
@@ -114,7 +115,7 @@ def main():
     n = wl.tokens * wl.d_model
     x_src, g_src = rn(shape, 1.0), rn(shape, wl.grad_sigma)
     cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
-                         wl.ln_eps)
+                         wl.ln_eps, wl.block)
     ws = torch.empty(max(sw.swarm_stage_coded_workspace_bytes(cfg, True), sw.swarm_stage_coded_workspace_bytes(cfg, False)),
                      dtype=torch.uint8, device=dev)
     x, G, y, gin = (torch.empty(shape, dtype=dt, device=dev) for _ in range(4))
@@ -219,7 +220,7 @@ def main():
            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": wl.dtype, "data": "synthetic",
-           "config": {"workload": wl.name, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ffn": wl.d_ffn,
+           "config": {"workload": wl.name, "block": wl.block, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ffn": wl.d_ffn,
                       "seq": wl.seq, "microbatch": wl.batch, "blocks": wl.n_layers, "repeat": wl.n_repeat,
                       "codec": ("int8 absmax block 64 on stage input/output and their gradients, "
                                 + ("separate kernels" if args.unfused_codec else "fused into the stage boundary"))

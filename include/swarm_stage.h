@@ -44,6 +44,12 @@ typedef enum {
 
 typedef enum { SWARM_F32 = 0, SWARM_BF16 = 1 } swarm_dtype;
 
+/* Which Transformer block the stage applies.
+ *   SWARM_BLOCK_GELU         : the layer of the appendix "Additional Details for Section 4.1".
+ *   SWARM_BLOCK_ROTARY_GEGLU : the layer of the large-scale model (appendix "Additional Details for
+ *     Section 4.3": the standard layer with rotary position embeddings and GeGLU activations). */
+typedef enum { SWARM_BLOCK_GELU = 0, SWARM_BLOCK_ROTARY_GEGLU = 1 } swarm_block_kind;
+
 /* Shape of a stage.  Constraints: d_model % n_heads == 0; d_model / n_heads is 64
  * or 128; d_model % 64 == 0; d_ffn % 64 == 0; all counts >= 1; seq >= 1.
  * The stage applies parameter set 0 n_repeat times, then set 1 n_repeat times,
@@ -55,6 +61,7 @@ typedef struct {
   int32_t batch, seq;        /* microbatch B, sequence length S                    */
   int32_t dtype;             /* swarm_dtype of x, grads w.r.t. x and parameters    */
   float   ln_eps;            /* LayerNorm epsilon, inside the square root          */
+  int32_t block_kind;        /* swarm_block_kind                                   */
 } swarm_stage_config;
 
 /* One pre-LayerNorm Transformer block (the layer of the appendix "Additional
@@ -64,13 +71,19 @@ typedef struct {
  *   c = LN(h; ln2_g, ln2_b);  y = h + gelu(c w_1^T + b_1) w_2^T + b_2   (erf GeLU).
  * Weights are [out, in]; rows 0..d-1 of w_qkv produce q, d..2d-1 k, 2d..3d-1 v;
  * head h owns columns h*d_head .. (h+1)*d_head-1 of q, k, v and o.
+ * With SWARM_BLOCK_ROTARY_GEGLU two steps change:
+ *   - before the softmax, the pairs (t[2i], t[2i+1]), i < d_head/2, of every head of q and of k at sequence
+ *     position pos (0-based, restarting in every sequence of the microbatch) are rotated by the angle
+ *     pos * 10000^(-2i/d_head):  t[2i]' = t[2i] cos - t[2i+1] sin,  t[2i+1]' = t[2i] sin + t[2i+1] cos;
+ *   - w_1 is [2f, d] and b_1 [2f] (rows 0..f-1 = gate, f..2f-1 = up):  u = c w_1^T + b_1,
+ *     y = h + (gelu(u[:f]) * u[f:]) w_2^T + b_2.
  * Element type = config.dtype. */
 typedef struct {
   const void *ln1_g, *ln1_b;   /* [d]           */
   const void *w_qkv, *b_qkv;   /* [3d, d], [3d] */
   const void *w_o,   *b_o;     /* [d, d],  [d]  */
   const void *ln2_g, *ln2_b;   /* [d]           */
-  const void *w_1,   *b_1;     /* [f, d],  [f]  */
+  const void *w_1,   *b_1;     /* [f, d],  [f]   ([2f, d], [2f] for the GeGLU block) */
   const void *w_2,   *b_2;     /* [d, f],  [d]  */
 } swarm_block_params;
 

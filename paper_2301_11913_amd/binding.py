@@ -8,6 +8,7 @@ from typing import Dict, List, Optional, Sequence
 import torch
 
 SWARM_F32, SWARM_BF16 = 0, 1
+SWARM_BLOCK_GELU, SWARM_BLOCK_ROTARY_GEGLU = 0, 1
 PARAM_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                 "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm_stage_backward",
@@ -26,7 +27,7 @@ class SwarmError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ffn", C.c_int32),
                 ("n_layers", C.c_int32), ("n_repeat", C.c_int32), ("batch", C.c_int32),
-                ("seq", C.c_int32), ("dtype", C.c_int32), ("ln_eps", C.c_float)]
+                ("seq", C.c_int32), ("dtype", C.c_int32), ("ln_eps", C.c_float), ("block_kind", C.c_int32)]
 
 
 class _BlockPtrs(C.Structure):
@@ -36,12 +37,15 @@ class _BlockPtrs(C.Structure):
 class StageConfig:
     """Host-side description of a stage (mirrors swarm_stage_config)."""
 
-    def __init__(self, d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps=1e-5):
+    def __init__(self, d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps=1e-5,
+                 block_kind=SWARM_BLOCK_GELU):
+        if isinstance(block_kind, str):
+            block_kind = {"gelu": SWARM_BLOCK_GELU, "rotary_geglu": SWARM_BLOCK_ROTARY_GEGLU}[block_kind]
         if isinstance(dtype, str):
             dtype = {"f32": SWARM_F32, "bf16": SWARM_BF16}[dtype]
         elif isinstance(dtype, torch.dtype):
             dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
-        self.c = _Config(d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps)
+        self.c = _Config(d_model, n_heads, d_ffn, n_layers, n_repeat, batch, seq, dtype, ln_eps, block_kind)
 
     @property
     def torch_dtype(self):

@@ -64,6 +64,19 @@ swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, fl
 size_t colsum_scratch_floats(int T, int N);
 swarm_status colsum_accum(const void* X, int T, int N, float* out, float* partial, bool bf16, hipStream_t st);
 
+// ------------------------------------------------------------------ rotary embedding / GeGLU
+// table [S, dh/2] of (cos, sin) fp32 pairs of pos * 10000^(-2i/dh); rope_table_floats(S, dh) floats.
+size_t rope_table_floats(int S, int dh);
+swarm_status rope_table(float* table, int S, int dh, hipStream_t st);
+// Rotates the pairs (2i, 2i+1) of every head of the q and k columns of qkv [T,3d] in place;
+// inverse = rotation by the negative angle (applied to dq, dk in the backward pass).
+swarm_status rope_apply(void* qkv, const float* table, int T, int S, int d, int dh, bool inverse, bool bf16,
+                        hipStream_t st);
+// u [T,2f] = gate | up.  g [T,f] = gelu(gate) * up.
+swarm_status geglu_fwd(const void* u, void* g, int T, int f, bool bf16, hipStream_t st);
+// du [T,2f] = dg * up * gelu'(gate) | dg * gelu(gate).
+swarm_status geglu_bwd(const void* dg, const void* u, void* du, int T, int f, bool bf16, hipStream_t st);
+
 // ------------------------------------------------------------------ attention
 // qkv [T,3d] (q | k | v along the last dim; head h = columns h*dh..), causal, scores scaled by 1/sqrt(dh).
 // o [T,d]; lse [B,H,S] fp32 = log-sum-exp of the scaled scores of each query row.

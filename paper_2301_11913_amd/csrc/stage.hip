@@ -16,6 +16,8 @@ namespace {
 
 struct Dims {
   int T, d, f, H, dh, B, S, apps;
+  int f1;     // rows of w_1: f, or 2f (gate | up) for the rotary + GeGLU block
+  bool rope_geglu;
   bool bf16;
   size_t es;  // element size of the activation dtype
 };
@@ -32,6 +34,7 @@ bool valid_config(const swarm_stage_config* c) {
   if ((long long)c->batch * c->seq > (1ll << 24)) return false;
   if (c->seq > 7000 && c->dtype == SWARM_F32) return false;   // direct attention keeps a score row in LDS
   if (!(c->ln_eps > 0.0f)) return false;
+  if (c->block_kind != SWARM_BLOCK_GELU && c->block_kind != SWARM_BLOCK_ROTARY_GEGLU) return false;
   return true;
 }
 
@@ -40,6 +43,8 @@ Dims dims_of(const swarm_stage_config* c) {
   D.B = c->batch; D.S = c->seq; D.T = c->batch * c->seq; D.d = c->d_model; D.f = c->d_ffn; D.H = c->n_heads;
   D.dh = D.d / D.H; D.apps = c->n_layers * c->n_repeat; D.bf16 = c->dtype == SWARM_BF16;
   D.es = D.bf16 ? 2 : 4;
+  D.rope_geglu = c->block_kind == SWARM_BLOCK_ROTARY_GEGLU;
+  D.f1 = D.rope_geglu ? 2 * D.f : D.f;
   return D;
 }
 
@@ -62,12 +67,14 @@ struct Saved {
   const void* x;   // block input [T,d]
   void *a, *qkv, *o, *h, *c, *u, *g;
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
+  const float* rope;   // (cos, sin) table shared by all applications; nullptr for the GeLU block
 };
 
 void carve_saved(Carver& cv, const Dims& D, Saved& s, bool want_u) {
   const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
   s.a = cv.take(Td); s.qkv = cv.take(3 * Td); s.o = cv.take(Td); s.h = cv.take(Td); s.c = cv.take(Td);
-  s.u = want_u ? cv.take(Tf) : nullptr;
+  // the GeGLU block always materialises u = gate | up; the GeLU block needs u only for the backward pass
+  s.u = (want_u || D.rope_geglu) ? cv.take((size_t)D.T * D.f1 * D.es) : nullptr;
   s.g = cv.take(Tf);
   s.mean1 = (float*)cv.take((size_t)D.T * 4); s.rstd1 = (float*)cv.take((size_t)D.T * 4);
   s.mean2 = (float*)cv.take((size_t)D.T * 4); s.rstd2 = (float*)cv.take((size_t)D.T * 4);
@@ -104,6 +111,7 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   q.M = T; q.N = 3 * d; q.K = d; q.A = s.a; q.lda = d; q.B = p.w_qkv; q.ldb = d; q.C = s.qkv; q.ldc = 3 * d;
   q.epilogue = EPI_BIAS; q.bias = p.b_qkv;
   SWARM_TRY(gemm(D, q, st));
+  if (D.rope_geglu) SWARM_TRY(rope_apply(s.qkv, s.rope, T, D.S, d, D.dh, false, D.bf16, st));
   SWARM_TRY(attention_fwd(s.qkv, s.o, s.lse, D.B, D.S, D.H, D.dh, D.bf16, st));
   GemmArgs o{};
   o.M = T; o.N = d; o.K = d; o.A = s.o; o.lda = d; o.B = p.w_o; o.ldb = d; o.C = s.h; o.ldc = d;
@@ -113,7 +121,13 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   GemmArgs f1{};
   f1.M = T; f1.N = f; f1.K = d; f1.A = s.c; f1.lda = d; f1.B = p.w_1; f1.ldb = d; f1.C = s.g; f1.ldc = f;
   f1.epilogue = EPI_BIAS_GELU; f1.bias = p.b_1; f1.C2 = s.u; f1.ldc2 = f;
-  SWARM_TRY(gemm(D, f1, st));
+  if (D.rope_geglu) {
+    f1.N = 2 * f; f1.C = s.u; f1.ldc = 2 * f; f1.epilogue = EPI_BIAS; f1.C2 = nullptr;
+    SWARM_TRY(gemm(D, f1, st));
+    SWARM_TRY(geglu_fwd(s.u, s.g, T, f, D.bf16, st));
+  } else {
+    SWARM_TRY(gemm(D, f1, st));
+  }
   if (y || bd.out_codes) {
     GemmArgs f2{};
     f2.M = T; f2.N = d; f2.K = f; f2.A = s.g; f2.lda = f; f2.B = p.w_2; f2.ldb = f; f2.C = y; f2.ldc = d;
@@ -126,6 +140,7 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
 
 struct BwdTemps {
   void *du, *dc, *dh, *dout, *dqkv, *da;
+  void* dg;   // GeGLU block only: gradient of g [T,f]
   float *delta, *partial;
 };
 
@@ -154,10 +169,15 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
   const int d = D.d, f = D.f;
   // y = h + gelu(u) W2^T + b2
   SWARM_TRY(weight_grads(D, dy, d, s.g, f, gp.w_2, gp.b_2, t.partial, st));
-  SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.du, EPI_DGELU, s.u, st));
+  if (D.rope_geglu) {
+    SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.dg, EPI_STORE, nullptr, st));
+    SWARM_TRY(geglu_bwd(t.dg, s.u, t.du, D.T, f, D.bf16, st));
+  } else {
+    SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.du, EPI_DGELU, s.u, st));
+  }
   // u = c W1^T + b1
-  SWARM_TRY(weight_grads(D, t.du, f, s.c, d, gp.w_1, gp.b_1, t.partial, st));
-  SWARM_TRY(data_grad(D, t.du, f, p.w_1, d, t.dc, EPI_STORE, nullptr, st));
+  SWARM_TRY(weight_grads(D, t.du, D.f1, s.c, d, gp.w_1, gp.b_1, t.partial, st));
+  SWARM_TRY(data_grad(D, t.du, D.f1, p.w_1, d, t.dc, EPI_STORE, nullptr, st));
   // c = LN2(h);  dh = dy + LN2'(dc)
   SWARM_TRY(layernorm_bwd(t.dc, s.h, s.mean2, s.rstd2, p.ln2_g, dy, t.dh, gp.ln2_g, gp.ln2_b, t.partial, D.T, d,
                           D.bf16, st));
@@ -165,6 +185,8 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
   SWARM_TRY(weight_grads(D, t.dh, d, s.o, d, gp.w_o, gp.b_o, t.partial, st));
   SWARM_TRY(data_grad(D, t.dh, d, p.w_o, d, t.dout, EPI_STORE, nullptr, st));
   SWARM_TRY(attention_bwd(s.qkv, s.o, t.dout, s.lse, t.delta, t.dqkv, D.B, D.S, D.H, D.dh, D.bf16, st));
+  // the saved q, k are the rotated ones: turn their gradients back
+  if (D.rope_geglu) SWARM_TRY(rope_apply(t.dqkv, s.rope, D.T, D.S, d, D.dh, true, D.bf16, st));
   // qkv = a Wqkv^T + bqkv
   SWARM_TRY(weight_grads(D, t.dqkv, 3 * d, s.a, d, gp.w_qkv, gp.b_qkv, t.partial, st));
   SWARM_TRY(data_grad(D, t.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
@@ -177,6 +199,7 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
 struct FwdPlan {
   Saved s;
   void* z[2];
+  float* rope;
 };
 
 size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
@@ -184,6 +207,8 @@ size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
   const size_t Td = (size_t)D.T * D.d * D.es;
   P.s = Saved{};
   carve_saved(cv, D, P.s, false);
+  P.rope = D.rope_geglu ? (float*)cv.take(rope_table_floats(D.S, D.dh) * 4) : nullptr;
+  P.s.rope = P.rope;
   P.z[0] = D.apps > 1 ? cv.take(Td) : nullptr;
   P.z[1] = D.apps > 1 ? cv.take(Td) : nullptr;
   return cv.total();
@@ -194,6 +219,7 @@ struct BwdPlan {
   std::vector<void*> xbuf;   // inputs of applications 1..apps-1
   BwdTemps t;
   void* dz[2];
+  float* rope;
 };
 
 size_t plan_backward(const Dims& D, void* ws, BwdPlan& P) {
@@ -201,15 +227,19 @@ size_t plan_backward(const Dims& D, void* ws, BwdPlan& P) {
   const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
   P.saved.assign(D.apps, Saved{});
   P.xbuf.assign(D.apps, nullptr);
+  P.rope = D.rope_geglu ? (float*)cv.take(rope_table_floats(D.S, D.dh) * 4) : nullptr;
   for (int i = 0; i < D.apps; ++i) {
     carve_saved(cv, D, P.saved[i], true);
+    P.saved[i].rope = P.rope;
     if (i > 0) P.xbuf[i] = cv.take(Td);
   }
-  P.t.du = cv.take(Tf); P.t.dc = cv.take(Td); P.t.dh = cv.take(Td); P.t.dout = cv.take(Td);
+  P.t.du = cv.take((size_t)D.T * D.f1 * D.es);
+  P.t.dg = D.rope_geglu ? cv.take(Tf) : nullptr;
+  P.t.dc = cv.take(Td); P.t.dh = cv.take(Td); P.t.dout = cv.take(Td);
   P.t.dqkv = cv.take(3 * Td); P.t.da = cv.take(Td);
   P.t.delta = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
   size_t pf = layernorm_bwd_scratch_floats(D.T, D.d);
-  pf = std::max(pf, colsum_scratch_floats(D.T, std::max(3 * D.d, D.f)));
+  pf = std::max(pf, colsum_scratch_floats(D.T, std::max(3 * D.d, D.f1)));
   P.t.partial = (float*)cv.take(pf * 4);
   P.dz[0] = D.apps > 1 ? cv.take(Td) : nullptr;
   P.dz[1] = D.apps > 1 ? cv.take(Td) : nullptr;
@@ -255,6 +285,7 @@ extern "C" swarm_status swarm_stage_forward(const swarm_stage_config* cfg, const
   FwdPlan P;
   if (plan_forward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
+  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
   const void* cur = x_in;
   int app = 0;
   for (int l = 0; l < cfg->n_layers; ++l)
@@ -283,6 +314,7 @@ extern "C" swarm_status swarm_stage_backward(const swarm_stage_config* cfg, cons
   BwdPlan P;
   if (plan_backward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
+  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
 
   // recompute the forward from the stage input, keeping every application's intermediates
   const void* cur = x_in;
@@ -345,6 +377,7 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
   }
   FwdPlan P;
   plan_forward(D, workspace, P);
+  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
   const void* cur = x_dec;
   int app = 0;
   for (int l = 0; l < cfg->n_layers; ++l)
@@ -389,6 +422,7 @@ extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg
   }
   BwdPlan P;
   plan_backward(D, workspace, P);
+  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
   const void* cur = x_in;
   int app = 0;
   for (int l = 0; l < cfg->n_layers; ++l)

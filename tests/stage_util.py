@@ -17,7 +17,7 @@ def run_gpu(wl, params, x, G, n_backward_calls=1, forward=True, backward=True):
     """Returns dict(x_out, grad_in, grads[list of dict]) as float64 numpy arrays."""
     import paper_2301_11913_amd as sw
     cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
-                         wl.ln_eps)
+                         wl.ln_eps, wl.block)
     dp = [{k: to_dev(p[k], wl) for k in sw.PARAM_FIELDS} for p in params]
     xd, Gd = to_dev(x, wl), to_dev(G, wl)
     out = {}
@@ -44,10 +44,11 @@ def run_gpu(wl, params, x, G, n_backward_calls=1, forward=True, backward=True):
 def run_oracle(wl, params, x, G, dt=np.float64, forward=True, backward=True):
     out = {}
     if forward:
-        out["x_out"] = osg.stage_forward(params, x, wl.n_heads, wl.n_repeat, wl.ln_eps, dt)
+        out["x_out"] = osg.stage_forward(params, x, wl.n_heads, wl.n_repeat, wl.ln_eps, dt, kind=wl.block)
     if backward:
         grads = osg.zero_grads(params, dt)
-        out["grad_in"] = osg.stage_backward(params, x, G, grads, wl.n_heads, wl.n_repeat, wl.ln_eps, dt)
+        out["grad_in"] = osg.stage_backward(params, x, G, grads, wl.n_heads, wl.n_repeat, wl.ln_eps, dt,
+                                               kind=wl.block)
         out["grads"] = grads
     return out
 

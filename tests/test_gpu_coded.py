@@ -19,7 +19,8 @@ def _run(wl, seed_shift=0):
     dev = lambda a: (torch.from_numpy(np.ascontiguousarray(a)).to(dt)).cuda()
     cx, sx = ocodec.encode(x.reshape(-1))
     cg, sg = ocodec.encode(G.reshape(-1))
-    cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype)
+    cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
+                         block_kind=wl.block)
     dp = [{k: dev(p[k]) for k in sw.PARAM_FIELDS} for p in params]
     n = x.size
     i8 = lambda: torch.full((n,), 55, dtype=torch.int8, device="cuda")
