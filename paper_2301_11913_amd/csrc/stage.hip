@@ -138,18 +138,27 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   return SWARM_OK;
 }
 
+// Scratch of one block_backward call (reused by every application).
 struct BwdTemps {
-  void *du, *dc, *dh, *dout, *dqkv, *da;
+  void *dc, *dout, *da;
   void* dg;   // GeGLU block only: gradient of g [T,f]
   float *delta, *partial;
 };
 
-// dW[out,in] += dY^T X  and  db[out] += colsum(dY)
-swarm_status weight_grads(const Dims& D, const void* dY, int n_out, const void* X, int n_in, float* dW, float* db,
-                          float* partial, hipStream_t st) {
-  SWARM_TRY(colsum_accum(dY, D.T, n_out, db, partial, D.bf16, st));
+// Gradients that feed the weight-gradient GEMMs of one application: the gradient of the block output (dy, given),
+// of the FFN pre-activation (du), of the hidden stream (dh) and of q|k|v (dqkv).  The applications of one
+// parameter set keep theirs in consecutive slots, so that the set's weight gradients are ONE product over all
+// its tokens (see set_weight_grads).
+struct AppGrads {
+  void *du, *dh, *dqkv;
+};
+
+// dW[out,in] += dY^T X  and  db[out] += colsum(dY)  over `rows` token rows
+swarm_status weight_grads(const Dims& D, int rows, const void* dY, int n_out, const void* X, int n_in, float* dW,
+                          float* db, float* partial, hipStream_t st) {
+  SWARM_TRY(colsum_accum(dY, rows, n_out, db, partial, D.bf16, st));
   GemmArgs w{};
-  w.M = n_out; w.N = n_in; w.K = D.T; w.A = dY; w.lda = n_out; w.a_trans = true; w.B = X; w.ldb = n_in;
+  w.M = n_out; w.N = n_in; w.K = rows; w.A = dY; w.lda = n_out; w.a_trans = true; w.B = X; w.ldb = n_in;
   w.b_trans = true; w.C = dW; w.ldc = n_in; w.epilogue = EPI_ACCUM_F32;
   return gemm(D, w, st);
 }
@@ -163,36 +172,48 @@ swarm_status data_grad(const Dims& D, const void* dY, int n_out, const void* W, 
   return gemm(D, g, st);
 }
 
+// Data gradients and LayerNorm parameter gradients of one application; the matrix weight / bias gradients are
+// left to set_weight_grads, which reads dy and the tensors stored in `ag`.
 swarm_status block_backward(const Dims& D, const swarm_block_params& p, const swarm_block_grads& gp, const Saved& s,
-                            const BwdTemps& t, const void* dy, void* dx, hipStream_t st, int8_t* dx_codes = nullptr,
-                            float* dx_scales = nullptr) {
+                            const BwdTemps& t, const AppGrads& ag, const void* dy, void* dx, hipStream_t st,
+                            int8_t* dx_codes = nullptr, float* dx_scales = nullptr) {
   const int d = D.d, f = D.f;
-  // y = h + gelu(u) W2^T + b2
-  SWARM_TRY(weight_grads(D, dy, d, s.g, f, gp.w_2, gp.b_2, t.partial, st));
+  // y = h + g W2^T + b2,  g = gelu(u)  or  gelu(u_gate) * u_up
   if (D.rope_geglu) {
     SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.dg, EPI_STORE, nullptr, st));
-    SWARM_TRY(geglu_bwd(t.dg, s.u, t.du, D.T, f, D.bf16, st));
+    SWARM_TRY(geglu_bwd(t.dg, s.u, ag.du, D.T, f, D.bf16, st));
   } else {
-    SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.du, EPI_DGELU, s.u, st));
+    SWARM_TRY(data_grad(D, dy, d, p.w_2, f, ag.du, EPI_DGELU, s.u, st));
   }
   // u = c W1^T + b1
-  SWARM_TRY(weight_grads(D, t.du, D.f1, s.c, d, gp.w_1, gp.b_1, t.partial, st));
-  SWARM_TRY(data_grad(D, t.du, D.f1, p.w_1, d, t.dc, EPI_STORE, nullptr, st));
+  SWARM_TRY(data_grad(D, ag.du, D.f1, p.w_1, d, t.dc, EPI_STORE, nullptr, st));
   // c = LN2(h);  dh = dy + LN2'(dc)
-  SWARM_TRY(layernorm_bwd(t.dc, s.h, s.mean2, s.rstd2, p.ln2_g, dy, t.dh, gp.ln2_g, gp.ln2_b, t.partial, D.T, d,
+  SWARM_TRY(layernorm_bwd(t.dc, s.h, s.mean2, s.rstd2, p.ln2_g, dy, ag.dh, gp.ln2_g, gp.ln2_b, t.partial, D.T, d,
                           D.bf16, st));
   // h = x + o Wo^T + bo
-  SWARM_TRY(weight_grads(D, t.dh, d, s.o, d, gp.w_o, gp.b_o, t.partial, st));
-  SWARM_TRY(data_grad(D, t.dh, d, p.w_o, d, t.dout, EPI_STORE, nullptr, st));
-  SWARM_TRY(attention_bwd(s.qkv, s.o, t.dout, s.lse, t.delta, t.dqkv, D.B, D.S, D.H, D.dh, D.bf16, st));
+  SWARM_TRY(data_grad(D, ag.dh, d, p.w_o, d, t.dout, EPI_STORE, nullptr, st));
+  SWARM_TRY(attention_bwd(s.qkv, s.o, t.dout, s.lse, t.delta, ag.dqkv, D.B, D.S, D.H, D.dh, D.bf16, st));
   // the saved q, k are the rotated ones: turn their gradients back
-  if (D.rope_geglu) SWARM_TRY(rope_apply(t.dqkv, s.rope, D.T, D.S, d, D.dh, true, D.bf16, st));
+  if (D.rope_geglu) SWARM_TRY(rope_apply(ag.dqkv, s.rope, D.T, D.S, d, D.dh, true, D.bf16, st));
   // qkv = a Wqkv^T + bqkv
-  SWARM_TRY(weight_grads(D, t.dqkv, 3 * d, s.a, d, gp.w_qkv, gp.b_qkv, t.partial, st));
-  SWARM_TRY(data_grad(D, t.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
+  SWARM_TRY(data_grad(D, ag.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
   // a = LN1(x);  dx = dh + LN1'(da)
-  SWARM_TRY(layernorm_bwd(t.da, s.x, s.mean1, s.rstd1, p.ln1_g, t.dh, dx, gp.ln1_g, gp.ln1_b, t.partial, D.T, d,
+  SWARM_TRY(layernorm_bwd(t.da, s.x, s.mean1, s.rstd1, p.ln1_g, ag.dh, dx, gp.ln1_g, gp.ln1_b, t.partial, D.T, d,
                           D.bf16, st, dx_codes, dx_scales));
+  return SWARM_OK;
+}
+
+// Weight and bias gradients of one parameter set over `n` consecutive applications whose tensors start at the
+// given pointers (slot pitch = one application's tensor): with layer sharing (Sections 2.3 and 4.3) the sum over
+// the applications is the K dimension of a single product, dW += [dY_0; ...; dY_{n-1}]^T [X_0; ...; X_{n-1}],
+// so the fp32 gradient matrix is read and written once per set instead of once per application.
+swarm_status set_weight_grads(const Dims& D, const swarm_block_grads& gp, int n, const void* dy, const AppGrads& ag,
+                              const Saved& s, float* partial, hipStream_t st) {
+  const int rows = n * D.T, d = D.d;
+  SWARM_TRY(weight_grads(D, rows, dy, d, s.g, D.f, gp.w_2, gp.b_2, partial, st));
+  SWARM_TRY(weight_grads(D, rows, ag.du, D.f1, s.c, d, gp.w_1, gp.b_1, partial, st));
+  SWARM_TRY(weight_grads(D, rows, ag.dh, d, s.o, d, gp.w_o, gp.b_o, partial, st));
+  SWARM_TRY(weight_grads(D, rows, ag.dqkv, 3 * d, s.a, d, gp.w_qkv, gp.b_qkv, partial, st));
   return SWARM_OK;
 }
 
@@ -214,36 +235,105 @@ size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
   return cv.total();
 }
 
+// Token rows per weight-gradient product (a longer run of shared applications is cut into several products).
+constexpr long long kMaxWgradRows = 1ll << 22;
+
+int wgrad_chunk(const Dims& D, int R) {
+  return (int)std::max<long long>(1, std::min<long long>(R, kMaxWgradRows / D.T));
+}
+
 struct BwdPlan {
   std::vector<Saved> saved;
   std::vector<void*> xbuf;   // inputs of applications 1..apps-1
   BwdTemps t;
-  void* dz[2];
+  char *du_slots, *dh_slots, *dqkv_slots;   // [R] slots of [T,f1], [T,d], [T,3d]: one per application of a set
+  char* dys[2];              // [R] slots of [T,d] (gradient of each application's output), by parameter-set parity
   float* rope;
 };
 
-size_t plan_backward(const Dims& D, void* ws, BwdPlan& P) {
+size_t plan_backward(const Dims& D, int L, int R, void* ws, BwdPlan& P) {
   Carver cv(ws);
-  const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
+  const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es, Tf1 = (size_t)D.T * D.f1 * D.es;
   P.saved.assign(D.apps, Saved{});
   P.xbuf.assign(D.apps, nullptr);
   P.rope = D.rope_geglu ? (float*)cv.take(rope_table_floats(D.S, D.dh) * 4) : nullptr;
+  // the right-hand operands of the weight-gradient products are contiguous over the applications
+  char* a_all = (char*)cv.take(D.apps * Td);
+  char* o_all = (char*)cv.take(D.apps * Td);
+  char* c_all = (char*)cv.take(D.apps * Td);
+  char* g_all = (char*)cv.take(D.apps * Tf);
   for (int i = 0; i < D.apps; ++i) {
-    carve_saved(cv, D, P.saved[i], true);
-    P.saved[i].rope = P.rope;
+    Saved& s = P.saved[i];
+    s.a = a_all ? a_all + i * Td : nullptr; s.o = o_all ? o_all + i * Td : nullptr;
+    s.c = c_all ? c_all + i * Td : nullptr; s.g = g_all ? g_all + i * Tf : nullptr;
+    s.qkv = cv.take(3 * Td); s.h = cv.take(Td); s.u = cv.take(Tf1);
+    s.mean1 = (float*)cv.take((size_t)D.T * 4); s.rstd1 = (float*)cv.take((size_t)D.T * 4);
+    s.mean2 = (float*)cv.take((size_t)D.T * 4); s.rstd2 = (float*)cv.take((size_t)D.T * 4);
+    s.lse = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
+    s.rope = P.rope;
     if (i > 0) P.xbuf[i] = cv.take(Td);
   }
-  P.t.du = cv.take((size_t)D.T * D.f1 * D.es);
+  P.du_slots = (char*)cv.take(R * Tf1); P.dh_slots = (char*)cv.take(R * Td); P.dqkv_slots = (char*)cv.take(R * 3 * Td);
+  P.dys[0] = D.apps > 1 ? (char*)cv.take(R * Td) : nullptr;
+  P.dys[1] = L > 1 ? (char*)cv.take(R * Td) : nullptr;
   P.t.dg = D.rope_geglu ? cv.take(Tf) : nullptr;
-  P.t.dc = cv.take(Td); P.t.dh = cv.take(Td); P.t.dout = cv.take(Td);
-  P.t.dqkv = cv.take(3 * Td); P.t.da = cv.take(Td);
+  P.t.dc = cv.take(Td); P.t.dout = cv.take(Td); P.t.da = cv.take(Td);
   P.t.delta = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
   size_t pf = layernorm_bwd_scratch_floats(D.T, D.d);
-  pf = std::max(pf, colsum_scratch_floats(D.T, std::max(3 * D.d, D.f1)));
+  pf = std::max(pf, colsum_scratch_floats(wgrad_chunk(D, R) * D.T, std::max(3 * D.d, D.f1)));
   P.t.partial = (float*)cv.take(pf * 4);
-  P.dz[0] = D.apps > 1 ? cv.take(Td) : nullptr;
-  P.dz[1] = D.apps > 1 ? cv.take(Td) : nullptr;
   return cv.total();
+}
+
+// Recompute the forward from the stage input (keeping every application's intermediates), then the reverse
+// sweep.  grad_in == nullptr: the input gradient leaves int8-encoded in gin_codes / gin_scales.
+swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const swarm_block_params* params,
+                          const void* x_in, const void* grad_out, void* grad_in, int8_t* gin_codes,
+                          float* gin_scales, const swarm_block_grads* grad_params, const BwdPlan& P_in,
+                          hipStream_t st) {
+  BwdPlan P = P_in;
+  const int L = cfg->n_layers, R = cfg->n_repeat;
+  const size_t Td = (size_t)D.T * D.d * D.es, Tf1 = (size_t)D.T * D.f1 * D.es;
+  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
+  const void* cur = x_in;
+  int app = 0;
+  for (int l = 0; l < L; ++l)
+    for (int r = 0; r < R; ++r, ++app) {
+      P.saved[app].x = cur;
+      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];   // the stage output itself is not needed
+      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
+      cur = y;
+    }
+  // With sharing, the last application's output gradient joins the slots of its parameter set.
+  const bool direct = R == 1;   // the last set then reads grad_out in place
+  if (!direct &&
+      hipMemcpyAsync(P.dys[(L - 1) & 1] + (size_t)(R - 1) * Td, grad_out, Td, hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return SWARM_ERR_LAUNCH;
+  const int chunk = wgrad_chunk(D, R);
+  for (int l = L - 1; l >= 0; --l) {
+    char* base = P.dys[l & 1];
+    const bool from_caller = direct && l == L - 1;
+    for (int r = R - 1; r >= 0; --r) {
+      app = l * R + r;
+      const void* dy = from_caller ? grad_out : base + (size_t)r * Td;
+      const AppGrads ag{P.du_slots + (size_t)r * Tf1, P.dh_slots + (size_t)r * Td, P.dqkv_slots + (size_t)r * 3 * Td};
+      if (app == 0) {
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, ag, dy, grad_in, st,
+                                 grad_in ? nullptr : gin_codes, grad_in ? nullptr : gin_scales));
+      } else {
+        void* dx = r > 0 ? base + (size_t)(r - 1) * Td : P.dys[(l - 1) & 1] + (size_t)(R - 1) * Td;
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, ag, dy, dx, st));
+      }
+    }
+    for (int r0 = 0; r0 < R; r0 += chunk) {
+      const int n = std::min(chunk, R - r0);
+      const void* dy = from_caller ? grad_out : base + (size_t)r0 * Td;
+      const AppGrads ag{P.du_slots + (size_t)r0 * Tf1, P.dh_slots + (size_t)r0 * Td,
+                        P.dqkv_slots + (size_t)r0 * 3 * Td};
+      SWARM_TRY(set_weight_grads(D, grad_params[l], n, dy, ag, P.saved[l * R + r0], P.t.partial, st));
+    }
+  }
+  return SWARM_OK;
 }
 
 bool params_ok(const swarm_block_params* p, int L) {
@@ -267,7 +357,7 @@ extern "C" size_t swarm_stage_workspace_bytes(const swarm_stage_config* cfg, int
   const Dims D = dims_of(cfg);
   if (for_backward) {
     BwdPlan P;
-    return plan_backward(D, nullptr, P);
+    return plan_backward(D, cfg->n_layers, cfg->n_repeat, nullptr, P);
   }
   FwdPlan P;
   return plan_forward(D, nullptr, P);
@@ -312,30 +402,9 @@ extern "C" swarm_status swarm_stage_backward(const swarm_stage_config* cfg, cons
     return SWARM_ERR_SHAPE;
   const Dims D = dims_of(cfg);
   BwdPlan P;
-  if (plan_backward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
-
-  // recompute the forward from the stage input, keeping every application's intermediates
-  const void* cur = x_in;
-  int app = 0;
-  for (int l = 0; l < cfg->n_layers; ++l)
-    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
-      P.saved[app].x = cur;
-      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];   // the stage output itself is not needed
-      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
-      cur = y;
-    }
-  // reverse sweep
-  const void* dy = grad_out;
-  app = D.apps - 1;
-  for (int l = cfg->n_layers - 1; l >= 0; --l)
-    for (int r = cfg->n_repeat - 1; r >= 0; --r, --app) {
-      void* dx = (app == 0) ? grad_in : P.dz[app & 1];
-      SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, dx, st));
-      dy = dx;
-    }
-  return SWARM_OK;
+  if (plan_backward(D, cfg->n_layers, cfg->n_repeat, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  return run_backward(D, cfg, params, x_in, grad_out, grad_in, nullptr, nullptr, grad_params, P,
+                      (hipStream_t)hip_stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -421,29 +490,6 @@ extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg
     return codec_encode_launch(gin, n, gin_codes, gin_scales, D.bf16, st);
   }
   BwdPlan P;
-  plan_backward(D, workspace, P);
-  if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
-  const void* cur = x_in;
-  int app = 0;
-  for (int l = 0; l < cfg->n_layers; ++l)
-    for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
-      P.saved[app].x = cur;
-      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];
-      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
-      cur = y;
-    }
-  const void* dy = tmp;
-  app = D.apps - 1;
-  for (int l = cfg->n_layers - 1; l >= 0; --l)
-    for (int r = cfg->n_repeat - 1; r >= 0; --r, --app) {
-      if (app == 0) {
-        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, nullptr, st, gin_codes,
-                                 gin_scales));
-      } else {
-        void* dx = P.dz[app & 1];
-        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, dy, dx, st));
-        dy = dx;
-      }
-    }
-  return SWARM_OK;
+  plan_backward(D, cfg->n_layers, cfg->n_repeat, workspace, P);
+  return run_backward(D, cfg, params, x_in, tmp, nullptr, gin_codes, gin_scales, grad_params, P, st);
 }

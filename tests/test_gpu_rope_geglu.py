@@ -125,7 +125,8 @@ def test_section43_stage_full_size():
     other arithmetic exact) already moves x_out by about 2.4e-2 of its maximum at this width: rounding errors
     of successive applications accumulate, the more so as the random-weight blocks amplify perturbations.  The
     2e-2 bar is therefore applied where it is meaningful, per application:
-      (1) the 16-deep call equals, bit for bit, the chain of 16 single-application calls;
+      (1) the 16-deep call equals the chain of 16 single-application calls (x_out and grad_in bit for bit, the
+          parameter gradients up to the fp32 summation order);
       (2) sampled applications of that chain (inputs taken from the chain itself, so they are the tensors the
           16-deep call really sees) match the oracle's single block within 2e-2, forward and backward;
       (3) end to end against the 16-deep fp32 oracle the deviation stays within 2e-2 * R/4, the bar of the
@@ -143,8 +144,10 @@ def test_section43_stage_full_size():
     # (1) composition
     xs, gs, gp = _gpu_chain(wl, params, x, G)
     assert np.array_equal(gpu["x_out"], xs[R]) and np.array_equal(gpu["grad_in"], gs[0])
+    # the 16-deep call sums a shared weight's gradient over all applications inside one product, the chain adds
+    # 16 fp32 results: same terms, another summation order
     for k in gp:
-        assert np.array_equal(gpu["grads"][0][k], gp[k]), k
+        assert max_norm_err(gpu["grads"][0][k], gp[k]) <= 1e-5, k
     print("16-deep call == chain of single applications", flush=True)
     # (2) per application against the oracle
     one = wl.replace(n_repeat=1)
