@@ -45,13 +45,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 // Issue the loads of one operand tile (BR rows of the GEMM x 32 k) into LDS at `lds` (BR*32 elements).
 // NW wavefronts share the BR/16 load instructions round-robin.
+// The t-th of this wavefront's BR*DBK/512/NW load instructions for the tile.
 template <int BR, int NW, bool TRANS>
-__device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
-                                           int wave, int lane) {
-  constexpr int NINST = BR * DBK / 512;
-  static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
-#pragma unroll
-  for (int t = 0; t < NINST / NW; ++t) {
+__device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
+                                               int wave, int lane, int t) {
+  {
     const int q = wave + t * NW;            // wave-uniform instruction index; fills lds + q*512 .. +512
     const bf16_raw* src;
     if constexpr (!TRANS) {
@@ -66,6 +64,15 @@ __device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int l
     }
     __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds + q * 512), 16, 0, 0);
   }
+}
+
+template <int BR, int NW, bool TRANS>
+__device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
+                                           int wave, int lane) {
+  constexpr int NINST = BR * DBK / 512;
+  static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
+#pragma unroll
+  for (int t = 0; t < NINST / NW; ++t) issue_tile_one<BR, NW, TRANS>(g, ld, r0, k0, lds, wave, lane, t);
 }
 
 // Fragment (32 GEMM rows x 16 k) for v_mfma_f32_32x32x16_bf16 from a non-transposed tile.
@@ -86,10 +93,22 @@ __device__ __forceinline__ bf16x8 frag_trans(const bf16_raw* tile, int col_base,
   const int off = chunk * 8 + (col & 4);
   const int krow = 16 * kk + 8 * lg + kq;
   const bf16_raw* p0 = tile + krow * BR + off;
-  const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)p0);
-  const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0 + 4 * BR));
-  uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
+  // Issued as plain instructions: behind the compiler's builtin for this read every pending global -> LDS load
+  // is taken as a possible writer of the bytes read and waited for (vmcnt(0)), which would serialise the loads
+  // of the next slice with the reads of this one.  The stages are disjoint by construction.  The price: the
+  // compiler does not count these reads, so the caller waits for them itself (lds_reads_done) before use.
+  const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p0;
+  uint2 a, b;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(a) : "v"(addr) : "memory");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(b) : "v"(addr), "n"(8 * BR) : "memory");
   return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
+}
+
+// All LDS reads of this wavefront have returned (also those the compiler does not know of); nothing is
+// scheduled across.
+__device__ __forceinline__ void lds_reads_done() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
@@ -119,14 +138,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int KT = p.K / DBK;
-  auto issue = [&](int kt) {
-    bf16_raw* st = lds + (kt % NS) * STAGE;
+  auto issue = [&](int kt, int stage) {   // slice kt -> LDS stage `stage`
+    bf16_raw* st = lds + stage * STAGE;
     issue_tile<BM, NW, A_T>(p.A, p.lda, m0, kt * DBK, st, wave, lane);
     issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, kt * DBK, st + BM * DBK, wave, lane);
   };
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) issue(s);
+    if (s < KT) issue(s, s);
   if (KT >= NS - 1) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 
@@ -151,31 +170,65 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
       for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
-  // Software pipeline: the fragments of sub-step kk+1 are read while sub-step kk is multiplied, and the
-  // last sub-step of a slice is multiplied AFTER the barrier, behind the reads of the next slice's
-  // first fragments, so the matrix pipe has work queued across the barrier.
+  // Software pipeline, written out instruction by instruction: every MFMA of sub-step kk is followed by one
+  // LDS read of a fragment of sub-step kk+1 (and, in the first sub-step of a slice, by this wavefront's next
+  // global -> LDS load of slice kt+1), and a scheduling barrier keeps that order.  Reads are thus spread under
+  // the multiplies and the waits in front of the next sub-step are partial.  The last sub-step of a slice is
+  // multiplied AFTER the barrier, behind the reads of the next slice's first fragments, so the matrix pipe has
+  // work queued across the barrier.  The loop body is one basic block: the last iteration re-fetches the last
+  // slice into the free stage instead of branching.
+  constexpr int NMMA = FM * FN, NF = FM + FN;
+  constexpr int IPA = BM * DBK / 512 / NW;          // this wavefront's load instructions for the A tile
+  constexpr int LPM = (IPW + NMMA - 1) / NMMA;      // loads behind one MFMA
+  static_assert(NMMA >= NF, "one fragment read per MFMA");
+  // reads in the order the next sub-step needs them: A row 0, all of B, the other A rows
+  auto read_nth = [&](const bf16_raw* sA, const bf16_raw* sB, int kk, int n, bf16x8 (&a)[FM], bf16x8 (&b)[FN]) {
+    if (n == 0 || n > FN) {
+      const int i = n == 0 ? 0 : n - FN;
+      if constexpr (A_T) a[i] = frag_trans<BM>(sA, wm * WTM + i * 32, kk, lane);
+      else a[i] = frag_rows(sA, wm * WTM + i * 32, kk, l32, lg);
+    } else {
+      const int j = n - 1;
+      if constexpr (B_T) b[j] = frag_trans<BN>(sB, wn * WTN + j * 32, kk, lane);
+      else b[j] = frag_rows(sB, wn * WTN + j * 32, kk, l32, lg);
+    }
+  };
+  // multiply (ca, cb); read the fragments of sub-step nkk of the tile at nA into (na, nb); with LOADS, issue the
+  // loads of slice `lk` into stage `ls`
+  auto substep = [&](const bf16x8 (&ca)[FM], const bf16x8 (&cb)[FN], const bf16_raw* nA, int nkk, bf16x8 (&na)[FM],
+                     bf16x8 (&nb)[FN], bool loads, int lk, int ls) {
+    bf16_raw* st = lds + ls * STAGE;
+    if constexpr (A_T || B_T) lds_reads_done();   // (ca, cb) were read by the previous sub-step
+#pragma unroll
+    for (int n = 0; n < NMMA; ++n) {
+      const int i = n / FN, j = n % FN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      if (n < NF) read_nth(nA, nA + BM * DBK, nkk, n, na, nb);
+      if (loads) {
+#pragma unroll
+        for (int t = n * LPM; t < (n + 1) * LPM && t < IPW; ++t) {
+          if (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+          else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   bf16x8 fa[2][FM], fb[2][FN];
   load_frags(lds, lds + BM * DBK, 0, fa[0], fb[0]);
   for (int kt = 0; kt < KT; ++kt) {
-    const bool more = kt + 1 < KT;
-    if (more) issue(kt + 1);            // refills the stage whose reads all completed before the last barrier
     const bf16_raw* sA = lds + (kt & 1) * STAGE;
-    const bf16_raw* sB = sA + BM * DBK;
+    const bf16_raw* nA = lds + ((kt + 1) & 1) * STAGE;
 #pragma unroll
-    for (int kk = 0; kk + 1 < KK; ++kk) {
-      load_frags(sA, sB, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-      mma(fa[kk & 1], fb[kk & 1]);
-    }
+    for (int kk = 0; kk + 1 < KK; ++kk)   // the first sub-step also refills the stage freed at the last barrier
+      substep(fa[kk & 1], fb[kk & 1], sA, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1], kk == 0, min(kt + 1, KT - 1),
+              (kt + 1) & 1);
     // slice kt+1 must have landed (this wavefront's part) and this wavefront's reads of slice kt be complete;
     // then all wavefronts meet
     wait_vmcnt<0>();
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();
-    if (more) {
-      const bf16_raw* nA = lds + ((kt + 1) & 1) * STAGE;
-      load_frags(nA, nA + BM * DBK, 0, fa[0], fb[0]);
-    }
-    mma(fa[(KK - 1) & 1], fb[(KK - 1) & 1]);
+    substep(fa[(KK - 1) & 1], fb[(KK - 1) & 1], nA, 0, fa[0], fb[0], false, 0, 0);
   }
   __builtin_amdgcn_s_barrier();   // all MFMAs read registers only, but keep the epilogue's LDS reuse fenced
 
