@@ -143,10 +143,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
     issue_tile<BM, NW, A_T>(p.A, p.lda, m0, kt * DBK, st, wave, lane);
     issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, kt * DBK, st + BM * DBK, wave, lane);
   };
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) issue(s, s);
-  if (KT >= NS - 1) wait_vmcnt<(NS - 2) * IPW>(); else wait_vmcnt<0>();
+  // When is the stage that a barrier frees refilled?  EARLY: in the sub-step right behind that barrier (slices 0
+  // and 1 are requested up front, slice kt+2 behind the barrier that ends slice kt); otherwise one sub-step
+  // later, at the top of the next iteration.  Measured: EARLY gains 1-3 % on the 256 x 256 tile and loses 5 % on
+  // the 128 x 128 one (two workgroups per compute unit already overlap each other's loads).
+#ifndef SWARM_GEMM_EARLY
+#define SWARM_GEMM_EARLY (BM == 256)
+#endif
+  constexpr bool EARLY = SWARM_GEMM_EARLY;
+  issue(0, 0);
+  if constexpr (EARLY) {
+    issue(min(1, KT - 1), 1);
+    wait_vmcnt<IPW>();
+  } else {
+    wait_vmcnt<0>();
+  }
   __builtin_amdgcn_s_barrier();
 
   constexpr int KK = DBK / 16;
@@ -180,6 +191,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   constexpr int NMMA = FM * FN, NF = FM + FN;
   constexpr int IPA = BM * DBK / 512 / NW;          // this wavefront's load instructions for the A tile
   constexpr int LPM = (IPW + NMMA - 1) / NMMA;      // loads behind one MFMA
+  constexpr int RPM = 1;                            // fragment reads behind one MFMA (2 and 3 measured no faster)
   static_assert(NMMA >= NF, "one fragment read per MFMA");
   // reads in the order the next sub-step needs them: A row 0, all of B, the other A rows
   auto read_nth = [&](const bf16_raw* sA, const bf16_raw* sB, int kk, int n, bf16x8 (&a)[FM], bf16x8 (&b)[FN]) {
@@ -203,7 +215,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
     for (int n = 0; n < NMMA; ++n) {
       const int i = n / FN, j = n % FN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
-      if (n < NF) read_nth(nA, nA + BM * DBK, nkk, n, na, nb);
+#pragma unroll
+      for (int r = n * RPM; r < (n + 1) * RPM && r < NF; ++r) read_nth(nA, nA + BM * DBK, nkk, r, na, nb);
       if (loads) {
 #pragma unroll
         for (int t = n * LPM; t < (n + 1) * LPM && t < IPW; ++t) {
@@ -220,16 +233,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
     const bf16_raw* sA = lds + (kt & 1) * STAGE;
     const bf16_raw* nA = lds + ((kt + 1) & 1) * STAGE;
 #pragma unroll
-    for (int kk = 0; kk + 1 < KK; ++kk)   // the first sub-step also refills the stage freed at the last barrier
-      substep(fa[kk & 1], fb[kk & 1], sA, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1], kk == 0, min(kt + 1, KT - 1),
-              (kt + 1) & 1);
+    for (int kk = 0; kk + 1 < KK; ++kk)
+      substep(fa[kk & 1], fb[kk & 1], sA, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1], !EARLY && kk == 0,
+              min(kt + 1, KT - 1), (kt + 1) & 1);
     // slice kt+1 must have landed (this wavefront's part) and this wavefront's reads of slice kt be complete;
     // then all wavefronts meet
     wait_vmcnt<0>();
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();
-    substep(fa[(KK - 1) & 1], fb[(KK - 1) & 1], nA, 0, fa[0], fb[0], false, 0, 0);
+    // the stage of slice kt is free (the last iterations re-fetch the last slice instead of branching)
+    substep(fa[(KK - 1) & 1], fb[(KK - 1) & 1], nA, 0, fa[0], fb[0], EARLY, min(kt + 2, KT - 1), kt & 1);
   }
+  wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();   // all MFMAs read registers only, but keep the epilogue's LDS reuse fenced
 
   // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
