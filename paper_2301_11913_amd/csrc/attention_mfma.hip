@@ -36,6 +36,12 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }    // vmcnt(0) only
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }  // lgkmcnt(0) only
+// at most N LDS reads of this wavefront still in flight (LDS returns in order); nothing is scheduled across
+template <int N>
+__device__ __forceinline__ void wait_lds_reads() {
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   f32x2 v = {a, b};
@@ -99,6 +105,24 @@ struct Tile64 {
     const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
     return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
   }
+  // The same block, read with plain instructions (two LDS reads).  Behind the compiler's builtin every pending
+  // global -> LDS load counts as a possible writer of the bytes read and is waited for (vmcnt(0)), which would
+  // serialise the next tile's loads with this tile's reads; the stages are disjoint by construction.  The
+  // compiler does not count these reads: the caller waits for them itself (wait_lds_reads) before use.
+  static __device__ __forceinline__ bf16x8 cols_raw(const bf16_raw* tile, int cbase, int rbase, int lane) {
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int col = cbase + 16 * (grp & 1) + 4 * (l16 & 3);
+    const int r0 = rbase + 4 * (grp >> 1) + (l16 >> 2);
+    const int r1 = r0 + 8;
+    const bf16_raw* p0 = tile + r0 * DH + (((col >> 3) ^ swz<DH>(r0)) << 3) + (col & 4);
+    const bf16_raw* p1 = tile + r1 * DH + (((col >> 3) ^ swz<DH>(r1)) << 3) + (col & 4);
+    const uint32_t a0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p0;
+    const uint32_t a1 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p1;
+    uint2 a, b;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(a) : "v"(a0) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(b) : "v"(a1) : "memory");
+    return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
+  }
 };
 
 // 8 contraction values of row `row` (columns col ..) straight from global memory, zero past nrows
@@ -130,6 +154,24 @@ __device__ __forceinline__ void store_rowT(bf16_raw* row, const f32x16 (&acc)[DB
     }
 }
 
+// Workgroup -> (tile along the sequence, head, batch element) for a 1-D grid of nt * H * B workgroups.
+// Consecutive workgroup ids go round-robin over the 8 XCDs; the workgroups of one (batch, head) pair all read
+// the same K / V (or Q / dO) rows, so they are placed on ONE XCD (pair index mod 8), next to each other in that
+// XCD's launch order: its L2 then fetches those rows once.  Inside a pair the tile index runs as given.
+__device__ __forceinline__ void tile_head_batch(int nt, int H, int& tile, int& h, int& b) {
+  const int id = blockIdx.x, npair = gridDim.x / nt;
+  int pair, ti;
+  if ((npair & 7) == 0) {
+    const int j = id >> 3;
+    pair = (j / nt) * 8 + (id & 7);
+    ti = j % nt;
+  } else {
+    pair = id / nt;
+    ti = id % nt;
+  }
+  tile = ti; h = pair % H; b = pair / H;
+}
+
 // ---- forward ------------------------------------------------------------------------------------
 // grid (ceil(S/128), H, B); wavefront w owns query rows q0+32w .. q0+32w+31; KV tiles of 64.
 template <int DH>
@@ -142,7 +184,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int nqt = (S + 127) / 128;
+  int qi, h, b;
+  tile_head_batch(nqt, H, qi, h, b);
+  const int qt = nqt - 1 - qi;          // longest rows first
   const int d = H * DH, ld = 3 * d;
   const int q0 = qt * 128;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
@@ -176,14 +221,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
     const int kv0 = t * 64;
     if (t + 1 < ntile) issue(t + 1);
     if (kv0 <= wq_max) {
+      // S^T = K Q^T: NQK MFMAs, fragment n = (ks = n / 2, key block n % 2); the read of fragment n+PF sits behind
+      // MFMA n, so reads run PF multiplies ahead of their use
+      constexpr int NQK = 2 * KS, PF = 4, RING = 8;
       f32x16 s[2];
       zero(s);
+      bf16x8 kr[RING];
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
+      for (int n = 0; n < PF; ++n) kr[n] = T::rows(sK, 32 * (n & 1) + l32, 2 * (n >> 1) + lg);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sK, 32 * kb + l32, 2 * ks + lg), qf[ks], s[kb], 0,
-                                                          0, 0);
+      for (int n = 0; n < NQK; ++n) {
+        s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[n % RING], qf[n >> 1], s[n & 1], 0, 0, 0);
+        if (n + PF < NQK) {
+          const int f = n + PF;
+          kr[f % RING] = T::rows(sK, 32 * (f & 1) + l32, 2 * (f >> 1) + lg);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // O^T += V^T P^T: NPV MFMAs, fragment n = (dh block n % DB, key group n / DB); the first PF fragments of
+      // V^T are requested now and arrive under the softmax arithmetic
+      constexpr int NPV = 4 * DB;
+      bf16x8 vr[RING];
+#pragma unroll
+      for (int n = 0; n < PF; ++n) vr[n] = T::cols_raw(sV, 32 * (n % DB), 16 * (n / DB), lane);
       if (kv0 + 63 > wq_min) {   // tile touches the diagonal (or the sequence end): mask kv > q
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -199,9 +259,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-      const float mc = m_new * c;
+      // The running maximum only has to keep exp2 in range: it is raised (and O^T, l rescaled) only when some
+      // query of the wavefront exceeds its reference by more than 2^kSlack; until then p <= 2^kSlack.
+      constexpr float kSlack = 8.0f;
+      if (__builtin_amdgcn_ballot_w64((mx - m) * c > kSlack) != 0) {
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+        l *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      }
+      const float mc = m * c;
       float sum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -212,21 +283,26 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
           sum += p;
         }
       sum += __shfl_xor(sum, 32, 64);
-      l = l * alpha + sum;
-      m = m_new;
-#pragma unroll
-      for (int i = 0; i < DB; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      l += sum;
       bf16x8 pf[4];
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) pf[tt] = pack8(s[tt >> 1], 8 * (tt & 1));
 #pragma unroll
-      for (int i = 0; i < DB; ++i)
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt)
-          oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sV, 32 * i, 16 * tt, lane), pf[tt], oacc[i], 0, 0,
-                                                            0);
+      for (int n = 0; n < NPV; ++n) {
+        // fragments n+1 .. min(n+PF, NPV)-1 may still be in flight: two reads each
+        constexpr int kMaxAhead = PF - 1;
+        const int ahead = (NPV - 1 - n) < kMaxAhead ? (NPV - 1 - n) : kMaxAhead;
+        if (ahead == 3) wait_lds_reads<6>();
+        else if (ahead == 2) wait_lds_reads<4>();
+        else if (ahead == 1) wait_lds_reads<2>();
+        else wait_lds_reads<0>();
+        oacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[n % RING], pf[n / DB], oacc[n % DB], 0, 0, 0);
+        if (n + PF < NPV) {
+          const int f = n + PF;
+          vr[f % RING] = T::cols_raw(sV, 32 * (f % DB), 16 * (f / DB), lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     wait_vm0();
     wait_lgkm0();
@@ -284,7 +360,8 @@ __global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_
   const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int w = w8 & 3;
   const bool is_dk = w8 >= 4;
-  const int kb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int kb, h, b;
+  tile_head_batch((S + 127) / 128, H, kb, h, b);
   const int d = H * DH, ld = 3 * d;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
   const bf16_raw* K = Q + d;
@@ -392,7 +469,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int qtile = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int nqt = (S + 127) / 128;
+  int qi, h, b;
+  tile_head_batch(nqt, H, qi, h, b);
+  const int qtile = nqt - 1 - qi;       // longest rows first
   const int d = H * DH, ld = 3 * d;
   const int q0 = qtile * 128;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
@@ -486,8 +566,8 @@ swarm_status launch_fwd(const bf16_raw* qkv, bf16_raw* o, float* lse, int B, int
   constexpr size_t lds_bytes = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
   static bool a0 = false;
   if (set_lds(attn_fwd_kernel<DH>, lds_bytes, a0) != SWARM_OK) return SWARM_ERR_LAUNCH;
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((S + 127) / 128, H, B), dim3(kThreads), lds_bytes, st, qkv, o, lse,
-                     S, H);
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3(((S + 127) / 128) * H * B), dim3(kThreads), lds_bytes, st, qkv, o,
+                     lse, S, H);
   return launch_status();
 }
 
@@ -500,7 +580,7 @@ swarm_status launch_bwd(const bf16_raw* qkv, const bf16_raw* o, const bf16_raw* 
   if (set_lds(attn_bwd_dkdv_kernel<DH>, lds_dkdv, a1) != SWARM_OK) return SWARM_ERR_LAUNCH;
   if (set_lds(attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3(B * S), dim3(kThreads), 0, st, o, dout, delta, S, H);
-  dim3 grid((S + 127) / 128, H, B);
+  dim3 grid(((S + 127) / 128) * H * B);
   hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, grid, dim3(kDkDvThreads), lds_dkdv, st, qkv, dout, lse, delta, dqkv, S,
                      H);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, grid, dim3(kThreads), lds_dq, st, qkv, dout, lse, delta, dqkv, S, H);
