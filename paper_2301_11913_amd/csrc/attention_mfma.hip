@@ -408,40 +408,77 @@ __global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_
       const bool diag = q0 < wkv_min + 32;   // some q in the tile is below some kv of this wavefront
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
+        // S = Q K^T (both roles) and dP = dO V^T (dK role): fragment reads run PF MFMAs ahead of their use.
+        // dV role: N1 = KS fragments of Q rows; dK role: 2 KS fragments, Q rows (even) and dO rows (odd).
+        constexpr int PF = 3, RING = 4;
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        bf16x8 fr[RING];
+        if (is_dk) {
+          constexpr int N1 = 2 * KS;
+          auto frag1 = [&](int n) { return T::rows((n & 1) ? sdO : sQ, 32 * qb + l32, 2 * (n >> 1) + lg); };
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sQ, 32 * qb + l32, 2 * ks + lg), kf[ks], s, 0, 0, 0);
-          if (is_dk)
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sdO, 32 * qb + l32, 2 * ks + lg), vf[ks], dp, 0, 0, 0);
+          for (int n = 0; n < PF; ++n) fr[n] = frag1(n);
+#pragma unroll
+          for (int n = 0; n < N1; ++n) {
+            if (n & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], vf[n >> 1], dp, 0, 0, 0);
+            else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], kf[n >> 1], s, 0, 0, 0);
+            if (n + PF < N1) fr[(n + PF) % RING] = frag1(n + PF);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        } else {
+          constexpr int N1 = KS;
+          auto frag1 = [&](int n) { return T::rows(sQ, 32 * qb + l32, 2 * n + lg); };
+#pragma unroll
+          for (int n = 0; n < PF; ++n) fr[n] = frag1(n);
+#pragma unroll
+          for (int n = 0; n < N1; ++n) {
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], kf[n], s, 0, 0, 0);
+            if (n + PF < N1) fr[(n + PF) % RING] = frag1(n + PF);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
+        // dK^T += Q^T dS resp. dV^T += dO^T P: N2 MFMAs, fragment n = (dh block n % DB, query group n / DB); the
+        // first PF fragments are requested now and arrive under the softmax arithmetic
+        constexpr int N2 = 2 * DB;
+        const bf16_raw* src = is_dk ? sQ : sdO;
+        bf16x8 ct[RING];
+        auto frag2 = [&](int n) { return T::cols_raw(src, 32 * (n % DB), 32 * qb + 16 * (n / DB), lane); };
+#pragma unroll
+        for (int n = 0; n < PF; ++n) ct[n] = frag2(n);
+        // (the row statistics below are ordinary LDS loads issued AFTER those transpose reads: LDS returns in
+        // order, so whatever count the compiler waits for before using them only over-waits)
+        float Ls[16], Ds[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int rbase = 32 * qb + 8 * g + 4 * lg;
           const float4 L = *reinterpret_cast<const float4*>(sstat + rbase);
           const float4 D = *reinterpret_cast<const float4*>(sstat + 64 + rbase);
-          const float Ls[4] = {L.x, L.y, L.z, L.w}, Ds[4] = {D.x, D.y, D.z, D.w};
+          Ls[4 * g] = L.x; Ls[4 * g + 1] = L.y; Ls[4 * g + 2] = L.z; Ls[4 * g + 3] = L.w;
+          Ds[4 * g] = D.x; Ds[4 * g + 1] = D.y; Ds[4 * g + 2] = D.z; Ds[4 * g + 3] = D.w;
+        }
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[e] * kLog2e));
-            const int q = q0 + rbase + e;
-            if ((diag && kvrow > q) || q >= S) p = 0.f;
-            s[r] = is_dk ? p * (dp[r] - Ds[e]) : p;      // dS for the dK wavefront, P for the dV wavefront
-          }
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[r] * kLog2e));
+          const int q = q0 + 32 * qb + 8 * (r >> 2) + 4 * lg + (r & 3);
+          if ((diag && kvrow > q) || q >= S) p = 0.f;
+          s[r] = is_dk ? p * (dp[r] - Ds[r]) : p;      // dS for the dK wavefront, P for the dV wavefront
         }
         bf16x8 bf[2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) bf[tt] = pack8(s, 8 * tt);
-        const bf16_raw* src = is_dk ? sQ : sdO;
 #pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(src, 32 * i, 32 * qb + 16 * tt, lane), bf[tt],
-                                                             acc[i], 0, 0, 0);
+        for (int n = 0; n < N2; ++n) {
+          // fragments n+1 .. min(n+PF, N2)-1 may still be in flight: two reads each
+          const int ahead = (N2 - 1 - n) < (PF - 1) ? (N2 - 1 - n) : (PF - 1);
+          if (ahead == 2) wait_lds_reads<4>();
+          else if (ahead == 1) wait_lds_reads<2>();
+          else wait_lds_reads<0>();
+          acc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ct[n % RING], bf[n / DB], acc[n % DB], 0, 0, 0);
+          if (n + PF < N2) ct[(n + PF) % RING] = frag2(n + PF);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
     wait_vm0();
@@ -517,14 +554,30 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
       const bool diag = kv0 + 63 > wq_min;
 #pragma unroll
       for (int kb2 = 0; kb2 < 2; ++kb2) {
+        // S^T = K Q^T and dP^T = V dO^T: N1 MFMAs, fragment n = (ks = n / 2; n even: K rows, n odd: V rows);
+        // the read of fragment n+PF sits behind MFMA n
+        constexpr int N1 = 2 * KS, PF = 3, RING = 4;
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        bf16x8 fr[RING];
+        auto frag1 = [&](int n) { return T::rows((n & 1) ? sV : sK, 32 * kb2 + l32, 2 * (n >> 1) + lg); };
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sK, 32 * kb2 + l32, 2 * ks + lg), qf[ks], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::rows(sV, 32 * kb2 + l32, 2 * ks + lg), dof[ks], dp, 0, 0, 0);
+        for (int n = 0; n < PF; ++n) fr[n] = frag1(n);
+#pragma unroll
+        for (int n = 0; n < N1; ++n) {
+          if (n & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], dof[n >> 1], dp, 0, 0, 0);
+          else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n % RING], qf[n >> 1], s, 0, 0, 0);
+          if (n + PF < N1) fr[(n + PF) % RING] = frag1(n + PF);
+          __builtin_amdgcn_sched_barrier(0);
         }
+        // dQ^T += K^T dS^T: N2 MFMAs, fragment n = (dh block n % DB, key group n / DB); the first PF fragments of
+        // K^T are requested now and arrive under the softmax-gradient arithmetic
+        constexpr int N2 = 2 * DB;
+        bf16x8 kt[RING];
+        auto frag2 = [&](int n) { return T::cols_raw(sK, 32 * (n % DB), 32 * kb2 + 16 * (n / DB), lane); };
+#pragma unroll
+        for (int n = 0; n < PF; ++n) kt[n] = frag2(n);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -L2));
@@ -536,11 +589,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) dsf[tt] = pack8(dp, 8 * tt);
 #pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-            dqacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(T::cols(sK, 32 * i, 32 * kb2 + 16 * tt, lane), dsf[tt],
-                                                               dqacc[i], 0, 0, 0);
+        for (int n = 0; n < N2; ++n) {
+          // fragments n+1 .. min(n+PF, N2)-1 may still be in flight: two reads each
+          const int ahead = (N2 - 1 - n) < (PF - 1) ? (N2 - 1 - n) : (PF - 1);
+          if (ahead == 2) wait_lds_reads<4>();
+          else if (ahead == 1) wait_lds_reads<2>();
+          else wait_lds_reads<0>();
+          dqacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[n % RING], dsf[n / DB], dqacc[n % DB], 0, 0, 0);
+          if (n + PF < N2) kt[(n + PF) % RING] = frag2(n + PF);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
     wait_vm0();
