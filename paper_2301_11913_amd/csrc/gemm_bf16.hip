@@ -243,8 +243,15 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
     vec_ok = vec_ok && g.N % 8 == 0 && g.ldc % 8 == 0 && al16(g.C) && (!g.bias || al16(g.bias)) &&
              (!g.aux || (al16(g.aux) && g.ldaux % 8 == 0)) && (!g.C2 || (al16(g.C2) && g.ldc2 % 8 == 0));
   if (g.epilogue == EPI_BIAS_RESID_ENCODE && (!vec_ok || g.N % 64 || g.ldc != g.N || !g.scales)) return SWARM_ERR_SHAPE;
+  // epilogues that only the MFMA kernels have: refuse (before any launch) what they cannot take
+  const bool mfma_only = g.epilogue == EPI_BIAS_ROPE || g.epilogue == EPI_DGEGLU || g.epilogue == EPI_BIAS_GEGLU;
+  if (mfma_only && (!vec_ok || (g.a_trans && !g.b_trans))) return SWARM_ERR_SHAPE;
+  if (g.epilogue == EPI_BIAS_ROPE && (!g.rope || g.rope_S < 1 || g.rope_dh % 8 || g.rope_cols % 8)) return SWARM_ERR_SHAPE;
+  if (g.epilogue == EPI_DGEGLU && (g.split != g.N || !g.aux)) return SWARM_ERR_SHAPE;
   if (!vec_ok || (g.a_trans && !g.b_trans)) return gemm_generic(g, true, st);
   static const bool use_dma = std::getenv("SWARM_GEMM_NO_DMA") == nullptr;
+  if (g.epilogue == EPI_BIAS_GEGLU)   // needs the gathered B tile of the direct-to-LDS kernel
+    return use_dma ? gemm_bf16_dma(g, st) : SWARM_ERR_SHAPE;
   if (use_dma) {
     const swarm_status s = gemm_bf16_dma(g, st);   // tile-aligned shapes: pipelined direct-to-LDS kernel
     if (s != SWARM_ERR_SHAPE) return s;
@@ -254,6 +261,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
+  k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
   const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= 160) {
     k.tiles_m = (g.M + 255) / 256; k.tiles_n = (g.N + 255) / 256;

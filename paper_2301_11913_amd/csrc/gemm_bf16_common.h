@@ -19,6 +19,8 @@ struct KArgs {
   const bf16_raw* bias; const bf16_raw* aux; int ldaux;
   bf16_raw* C2; int ldc2;
   float* scales;   // EPI_BIAS_RESID_ENCODE
+  const float* rope; int rope_S, rope_dh, rope_cols;   // EPI_BIAS_ROPE
+  int split;       // EPI_DGEGLU, EPI_BIAS_GEGLU
   int tiles_m, tiles_n;
   int group_m;   // tile rows walked together (L2 reuse of the B panel)
 };
@@ -101,6 +103,44 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
     }
     return;
   }
+  if constexpr (FN == 2 && !GUARD) if (epi == EPI_BIAS_GEGLU) {
+    // The B tile was gathered so that this sub-tile's columns 0..31 are the gate and 32..63 the up pre-activations
+    // of the SAME 32 features col0 .. col0+31 (col0 counts features here).  4 lanes per row, 8 features each.
+    const int c4 = lane & 3, rsub = lane >> 2;
+    const int feat = col0 + 8 * c4;
+    float bg[8], bu[8];
+    unpack8(*reinterpret_cast<const uint4*>(p.bias + feat), bg);
+    unpack8(*reinterpret_cast<const uint4*>(p.bias + p.split + feat), bu);
+    bf16_raw* G = reinterpret_cast<bf16_raw*>(p.C);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+#pragma unroll
+      for (int ps = 0; ps < 2; ++ps) {
+        const int rl = ps * 16 + rsub;
+        const size_t row = row0 + i * 32 + rl;
+        const float* sp = stage + rl * kEpiPitch + 8 * c4;
+        const float4 g0 = *reinterpret_cast<const float4*>(sp), g1 = *reinterpret_cast<const float4*>(sp + 4);
+        const float4 u0 = *reinterpret_cast<const float4*>(sp + 32), u1 = *reinterpret_cast<const float4*>(sp + 36);
+        float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { g[e] += bg[e]; u[e] += bu[e]; }
+        if (p.C2) {
+          *reinterpret_cast<uint4*>(p.C2 + row * p.ldc2 + feat) = pack8_bf16(g);
+          *reinterpret_cast<uint4*>(p.C2 + row * p.ldc2 + p.split + feat) = pack8_bf16(u);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) g[e] = gelu_fast(g[e]) * u[e];
+        *reinterpret_cast<uint4*>(G + row * p.ldc + feat) = pack8_bf16(g);
+      }
+    }
+    return;
+  }
   constexpr int LPR = COLS / 8;          // lanes per row on the way out
   constexpr int RPP = 64 / LPR;          // rows per pass
   const int c8 = lane % LPR, rsub = lane / LPR;
@@ -109,7 +149,8 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
   float bias[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) bias[e] = 0.f;
-  if (col_ok && (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RESID_ENCODE))
+  if (col_ok && (epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RESID_ENCODE ||
+                 epi == EPI_BIAS_ROPE))
     unpack8(*reinterpret_cast<const uint4*>(p.bias + col), bias);
   bf16_raw* C = reinterpret_cast<bf16_raw*>(p.C);
 #pragma unroll
@@ -174,6 +215,31 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
         unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_fast(a[e]);
+      } else if (epi == EPI_BIAS_ROPE) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] += bias[e];
+        if (col < p.rope_cols) {   // pair (2i, 2i+1) of a head turns by pos * 10000^(-2i/d_head)
+          const int half = p.rope_dh >> 1;
+          const float* t = p.rope + 2 * ((size_t)(row % p.rope_S) * half + ((col % p.rope_dh) >> 1));
+          const float4 t0 = *reinterpret_cast<const float4*>(t), t1 = *reinterpret_cast<const float4*>(t + 4);
+          const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float a = x[2 * e], b = x[2 * e + 1];
+            x[2 * e] = a * cs[e] - b * sn[e];
+            x[2 * e + 1] = a * sn[e] + b * cs[e];
+          }
+        }
+      } else if (epi == EPI_DGEGLU) {
+        float gt[8], up[8], o2[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), gt);
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + p.split + col), up);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          o2[e] = x[e] * gelu_fast(gt[e]);
+          x[e] = x[e] * up[e] * gelu_grad_fast(gt[e]);
+        }
+        *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + p.split + col) = pack8_bf16(o2);
       }
       *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + col) = pack8_bf16(x);
     }

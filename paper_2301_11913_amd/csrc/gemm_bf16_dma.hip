@@ -46,16 +46,20 @@ __device__ __forceinline__ void wait_vmcnt() {
 // Issue the loads of one operand tile (BR rows of the GEMM x 32 k) into LDS at `lds` (BR*32 elements).
 // NW wavefronts share the BR/16 load instructions round-robin.
 // The t-th of this wavefront's BR*DBK/512/NW load instructions for the tile.
+// glu_split != 0 (GeGLU forward, B = W1 [2*split, K]): the tile's rows are gathered so that every 64-row group
+// (one wavefront column) holds 32 gate rows followed by the 32 up rows of the same features; r0 then counts
+// features: tile row 64*w + c -> W1 row r0 + 32*w + (c & 31) + (c >= 32 ? split : 0).
 template <int BR, int NW, bool TRANS>
 __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
-                                               int wave, int lane, int t) {
+                                               int wave, int lane, int t, int glu_split = 0) {
   {
     const int q = wave + t * NW;            // wave-uniform instruction index; fills lds + q*512 .. +512
     const bf16_raw* src;
     if constexpr (!TRANS) {
       const int row = q * (64 / KCH) + lane / KCH;
       const int chunk = (lane % KCH) ^ swz_rows(row);
-      src = g + (size_t)(r0 + row) * ld + k0 + chunk * 8;
+      const int grow = glu_split ? r0 + 32 * (row >> 6) + (row & 31) + ((row & 32) ? glu_split : 0) : r0 + row;
+      src = g + (size_t)grow * ld + k0 + chunk * 8;
     } else {
       constexpr int CPR = BR / 8;           // 16-byte chunks per k-row
       const int krow = q * (64 / CPR) + lane / CPR;
@@ -68,11 +72,11 @@ __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, i
 
 template <int BR, int NW, bool TRANS>
 __device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
-                                           int wave, int lane) {
+                                           int wave, int lane, int glu_split = 0) {
   constexpr int NINST = BR * DBK / 512;
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
 #pragma unroll
-  for (int t = 0; t < NINST / NW; ++t) issue_tile_one<BR, NW, TRANS>(g, ld, r0, k0, lds, wave, lane, t);
+  for (int t = 0; t < NINST / NW; ++t) issue_tile_one<BR, NW, TRANS>(g, ld, r0, k0, lds, wave, lane, t, glu_split);
 }
 
 // Fragment (32 GEMM rows x 16 k) for v_mfma_f32_32x32x16_bf16 from a non-transposed tile.
@@ -122,7 +126,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
 
   int tile_m, tile_n;
   tile_of_block(p, tile_m, tile_n);
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int m0 = tile_m * BM;
+  // GeGLU forward: a tile of BN gathered rows covers BN/2 features; n0 then counts features
+  const int glu = (!B_T && p.epilogue == EPI_BIAS_GEGLU) ? p.split : 0;
+  const int n0 = glu ? tile_n * (BN / 2) : tile_n * BN;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -141,7 +148,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   auto issue = [&](int kt, int stage) {   // slice kt -> LDS stage `stage`
     bf16_raw* st = lds + stage * STAGE;
     issue_tile<BM, NW, A_T>(p.A, p.lda, m0, kt * DBK, st, wave, lane);
-    issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, kt * DBK, st + BM * DBK, wave, lane);
+    issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, kt * DBK, st + BM * DBK, wave, lane, glu);
   };
   // When is the stage that a barrier frees refilled?  EARLY: in the sub-step right behind that barrier (slices 0
   // and 1 are requested up front, slice kt+2 behind the barrier that ends slice kt); otherwise one sub-step
@@ -221,7 +228,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
 #pragma unroll
         for (int t = n * LPM; t < (n + 1) * LPM && t < IPW; ++t) {
           if (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
-          else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA);
+          else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -248,7 +255,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   __builtin_amdgcn_s_barrier();   // all MFMAs read registers only, but keep the epilogue's LDS reuse fenced
 
   // every wavefront is past the last barrier: the operand stages are free to serve as epilogue patches
-  gemm_epilogue<FM, FN, false>(p, acc, m0 + wm * WTM, n0 + wn * WTN, l32, lg,
+  gemm_epilogue<FM, FN, false>(p, acc, m0 + wm * WTM, glu ? n0 + wn * (WTN / 2) : n0 + wn * WTN, l32, lg,
                                reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
 }
 
@@ -280,12 +287,14 @@ swarm_status launch_dma_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t s
 // Returns SWARM_ERR_SHAPE when the problem is not tile-aligned (the caller then uses the guarded kernel).
 swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   if (g.a_trans && !g.b_trans) return SWARM_ERR_SHAPE;
+  if (g.epilogue == EPI_BIAS_GEGLU && (g.a_trans || g.b_trans || g.N != 2 * g.split || g.split % 64)) return SWARM_ERR_SHAPE;
   if (g.K % DBK || g.lda % 8 || g.ldb % 8 || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return SWARM_ERR_SHAPE;
   KArgs k;
   k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
+  k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
   if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {
     k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
     return launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);

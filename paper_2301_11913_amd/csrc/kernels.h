@@ -19,7 +19,14 @@ enum GemmEpilogue {
   EPI_BIAS_GELU = 3,   // u = acc + bias[n]; C = gelu(u); C2 = u when C2 != nullptr
   EPI_DGELU = 4,       // C = acc * gelu'(aux[m,n])
   EPI_ACCUM_F32 = 5,   // C (fp32) += acc
-  EPI_BIAS_RESID_ENCODE = 6   // x = acc + bias[n] + aux[m,n] rounded to bf16, stored int8-encoded: C = codes, scales
+  EPI_BIAS_RESID_ENCODE = 6,  // x = acc + bias[n] + aux[m,n] rounded to bf16, stored int8-encoded: C = codes, scales
+  // The three below exist in the bf16 MFMA kernels only; gemm_bf16 returns SWARM_ERR_SHAPE (nothing launched)
+  // for a problem they cannot take, and the caller then uses the unfused kernels.
+  EPI_BIAS_ROPE = 7,          // C = acc + bias[n], columns n < rope_cols rotated pairwise (rotary embedding)
+  EPI_DGEGLU = 8,             // aux = u [M, 2*split]: C[m,n] = acc * u[m,split+n] * gelu'(u[m,n]),
+                              //                       C[m,split+n] = acc * gelu(u[m,n])        (N = split)
+  EPI_BIAS_GEGLU = 9          // B = W1 [2*split, K], N = 2*split: u = acc + bias over gate|up,
+                              // C[m,j] = gelu(u[m,j]) * u[m,split+j] (C is [M,split]), C2 = u when C2 != nullptr
 };
 
 struct GemmArgs {
@@ -32,6 +39,9 @@ struct GemmArgs {
   const void* aux; int ldaux;   // [M,N] residual or pre-activation, activation dtype
   void* C2; int ldc2;      // optional second output (pre-activation u)
   float* scales;           // EPI_BIAS_RESID_ENCODE: one fp32 scale per 64 consecutive elements of C (ldc == N)
+  const float* rope;       // EPI_BIAS_ROPE: (cos, sin) table [rope_S, rope_dh/2]; row m is at position m % rope_S,
+  int rope_S, rope_dh, rope_cols;   // a head spans rope_dh columns, columns >= rope_cols are left alone
+  int split;               // EPI_DGEGLU / EPI_BIAS_GEGLU: f, the width of the gate (and of the up) half
 };
 
 // T = float: plain FMA tiles (parity configuration); T = bf16: MFMA kernel.

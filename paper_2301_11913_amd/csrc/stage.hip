@@ -100,7 +100,7 @@ struct Boundary {
 
 // y = block(x): writes every intermediate into `s`; the last GEMM is skipped when y == nullptr.
 swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Saved& s, void* y, float eps,
-                           hipStream_t st, const Boundary& bd = Boundary()) {
+                           hipStream_t st, const Boundary& bd = Boundary(), bool want_u = true) {
   const int T = D.T, d = D.d, f = D.f;
   if (bd.in_codes)
     SWARM_TRY(layernorm_fwd_decode(bd.in_codes, bd.in_scales, const_cast<void*>(s.x), p.ln1_g, p.ln1_b, s.a, s.mean1,
@@ -110,8 +110,23 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   GemmArgs q{};
   q.M = T; q.N = 3 * d; q.K = d; q.A = s.a; q.lda = d; q.B = p.w_qkv; q.ldb = d; q.C = s.qkv; q.ldc = 3 * d;
   q.epilogue = EPI_BIAS; q.bias = p.b_qkv;
-  SWARM_TRY(gemm(D, q, st));
-  if (D.rope_geglu) SWARM_TRY(rope_apply(s.qkv, s.rope, T, D.S, d, D.dh, false, D.bf16, st));
+  if (D.rope_geglu) {
+    // rotary in the QKV epilogue (fp32, before the rounding to bf16) where the MFMA GEMM takes the shape
+    swarm_status fused = SWARM_ERR_SHAPE;
+    if (D.bf16) {
+      GemmArgs qr = q;
+      qr.epilogue = EPI_BIAS_ROPE; qr.rope = s.rope; qr.rope_S = D.S; qr.rope_dh = D.dh; qr.rope_cols = 2 * d;
+      fused = gemm(D, qr, st);
+    }
+    if (fused == SWARM_ERR_SHAPE) {
+      SWARM_TRY(gemm(D, q, st));
+      SWARM_TRY(rope_apply(s.qkv, s.rope, T, D.S, d, D.dh, false, D.bf16, st));
+    } else {
+      SWARM_TRY(fused);
+    }
+  } else {
+    SWARM_TRY(gemm(D, q, st));
+  }
   SWARM_TRY(attention_fwd(s.qkv, s.o, s.lse, D.B, D.S, D.H, D.dh, D.bf16, st));
   GemmArgs o{};
   o.M = T; o.N = d; o.K = d; o.A = s.o; o.lda = d; o.B = p.w_o; o.ldb = d; o.C = s.h; o.ldc = d;
@@ -122,9 +137,20 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   f1.M = T; f1.N = f; f1.K = d; f1.A = s.c; f1.lda = d; f1.B = p.w_1; f1.ldb = d; f1.C = s.g; f1.ldc = f;
   f1.epilogue = EPI_BIAS_GELU; f1.bias = p.b_1; f1.C2 = s.u; f1.ldc2 = f;
   if (D.rope_geglu) {
-    f1.N = 2 * f; f1.C = s.u; f1.ldc = 2 * f; f1.epilogue = EPI_BIAS; f1.C2 = nullptr;
-    SWARM_TRY(gemm(D, f1, st));
-    SWARM_TRY(geglu_fwd(s.u, s.g, T, f, D.bf16, st));
+    // gate * up in the FFN1 epilogue (u = gate | up is stored only when the caller keeps it for the backward)
+    swarm_status fused = SWARM_ERR_SHAPE;
+    if (D.bf16) {
+      GemmArgs fg = f1;
+      fg.N = 2 * f; fg.epilogue = EPI_BIAS_GEGLU; fg.split = f; fg.C2 = want_u ? s.u : nullptr; fg.ldc2 = 2 * f;
+      fused = gemm(D, fg, st);
+    }
+    if (fused == SWARM_ERR_SHAPE) {
+      f1.N = 2 * f; f1.C = s.u; f1.ldc = 2 * f; f1.epilogue = EPI_BIAS; f1.C2 = nullptr;
+      SWARM_TRY(gemm(D, f1, st));
+      SWARM_TRY(geglu_fwd(s.u, s.g, T, f, D.bf16, st));
+    } else {
+      SWARM_TRY(fused);
+    }
   } else {
     SWARM_TRY(gemm(D, f1, st));
   }
@@ -180,8 +206,20 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
   const int d = D.d, f = D.f;
   // y = h + g W2^T + b2,  g = gelu(u)  or  gelu(u_gate) * u_up
   if (D.rope_geglu) {
-    SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.dg, EPI_STORE, nullptr, st));
-    SWARM_TRY(geglu_bwd(t.dg, s.u, ag.du, D.T, f, D.bf16, st));
+    // du = (dg * up * gelu'(gate) | dg * gelu(gate)) in the epilogue of dg = dy W2
+    swarm_status fused = SWARM_ERR_SHAPE;
+    if (D.bf16) {
+      GemmArgs g{};
+      g.M = D.T; g.N = f; g.K = d; g.A = dy; g.lda = d; g.B = p.w_2; g.ldb = f; g.b_trans = true;
+      g.C = ag.du; g.ldc = 2 * f; g.epilogue = EPI_DGEGLU; g.aux = s.u; g.ldaux = 2 * f; g.split = f;
+      fused = gemm(D, g, st);
+    }
+    if (fused == SWARM_ERR_SHAPE) {
+      SWARM_TRY(data_grad(D, dy, d, p.w_2, f, t.dg, EPI_STORE, nullptr, st));
+      SWARM_TRY(geglu_bwd(t.dg, s.u, ag.du, D.T, f, D.bf16, st));
+    } else {
+      SWARM_TRY(fused);
+    }
   } else {
     SWARM_TRY(data_grad(D, dy, d, p.w_2, f, ag.du, EPI_DGELU, s.u, st));
   }
@@ -382,7 +420,7 @@ extern "C" swarm_status swarm_stage_forward(const swarm_stage_config* cfg, const
     for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
       void* y = (app == D.apps - 1) ? x_out : P.z[app & 1];
       P.s.x = cur;
-      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st));
+      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st, Boundary(), false));
       cur = y;
     }
   return SWARM_OK;
@@ -457,7 +495,7 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
       if (last) { bd.out_codes = y_codes; bd.out_scales = y_scales; }
       void* y = last ? nullptr : P.z[app & 1];
       P.s.x = cur;
-      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st, bd));
+      SWARM_TRY(block_forward(D, params[l], P.s, y, cfg->ln_eps, st, bd, false));
       cur = y;
     }
   return SWARM_OK;
