@@ -144,3 +144,52 @@ def codec_tensor(seed: int, n_elems: int, std: float = 1.0, bf16: bool = False,
                  name: str = "codec") -> np.ndarray:
     """Flat tensor with the value distribution of a boundary activation."""
     return normal(seed, name, (n_elems,), 0.0, std, bf16)
+
+
+# ----------------------------------------------------------------------------------------------------
+# Compression-aware stage boundary (appendix "Compression-Aware Architectures"): the sending stage maps its
+# output y [T, m] to z [T, c] (linear bottleneck or maxout), the receiving stage maps z back to [T, m].
+@dataclasses.dataclass(frozen=True)
+class BoundaryWorkload:
+    name: str
+    dtype: str            # "f32" | "bf16"
+    kind: str             # "bottleneck" | "maxout"
+    d_model: int          # m
+    d_comp: int           # c (bottleneck) or m / k (maxout)
+    tokens: int           # T = microbatch * sequence
+    grad_sigma: float
+    ln_eps: float = 1e-5
+    seed: int = BASE_SEED + 100
+
+    def replace(self, **kw) -> "BoundaryWorkload":
+        return dataclasses.replace(self, **kw)
+
+
+BOUNDARY_WORKLOADS = {
+    # the appendix evaluates both layers at a compression factor of 2 on sequences of 2048 tokens
+    "bottleneck2_bf16_d4096": BoundaryWorkload("bottleneck2_bf16_d4096", "bf16", "bottleneck", 4096, 2048, 8192, 1e-2,
+                                               seed=BASE_SEED + 101),
+    "maxout2_bf16_d4096": BoundaryWorkload("maxout2_bf16_d4096", "bf16", "maxout", 4096, 2048, 8192, 1e-2,
+                                           seed=BASE_SEED + 102),
+}
+
+
+def make_boundary_params(wl: BoundaryWorkload):
+    """(compress params, decompress params): fp32 arrays, bf16-rounded for bf16 workloads."""
+    bf = wl.dtype == "bf16"
+    m, c = wl.d_model, wl.d_comp
+    comp = {"ln_g": normal(wl.seed, "c.ln_g", (m,), 1.0, 0.02, bf), "ln_b": normal(wl.seed, "c.ln_b", (m,), 0.0, 0.02, bf)}
+    if wl.kind == "bottleneck":
+        comp["w_c"] = normal(wl.seed, "c.w_c", (c, m), 0.0, 0.02, bf)
+    dec = {"ln_g": normal(wl.seed, "d.ln_g", (c,), 1.0, 0.02, bf), "ln_b": normal(wl.seed, "d.ln_b", (c,), 0.0, 0.02, bf),
+           "w_d": normal(wl.seed, "d.w_d", (m, c), 0.0, 0.02, bf)}
+    return comp, dec
+
+
+def make_boundary_inputs(wl: BoundaryWorkload):
+    """y [T, m] (sender input), dz [T, c] (gradient arriving at the sender), z [T, c] (receiver input),
+    dx [T, m] (gradient arriving at the receiver)."""
+    bf = wl.dtype == "bf16"
+    T, m, c = wl.tokens, wl.d_model, wl.d_comp
+    return (normal(wl.seed, "y", (T, m), 0.0, 1.0, bf), normal(wl.seed, "dz", (T, c), 0.0, wl.grad_sigma, bf),
+            normal(wl.seed, "z", (T, c), 0.0, 1.0, bf), normal(wl.seed, "dx", (T, m), 0.0, wl.grad_sigma, bf))
