@@ -49,22 +49,37 @@ def maxout_bwd(dz, idx, k):
 
 
 # ------------------------------------------------------------------------------------------- sender
-def compress_forward(y, p, kind, d_comp, eps=1e-5, dt=np.float64, keep=False):
-    """y [T, m] -> z [T, d_comp].  p: ln_g, ln_b [m] and, for the bottleneck, w_c [d_comp, m]."""
+def _stored(a, store):
+    """a as the kernel holds it in memory: None = exact, "f32" / "bf16" = rounded to that type (nearest even)."""
+    if store is None:
+        return a
+    a32 = a.astype(np.float32)
+    if store == "bf16":
+        from oracle.codec import f32_to_bf16_bits, bf16_bits_to_f32
+        a32 = bf16_bits_to_f32(f32_to_bf16_bits(a32))
+    return a32.astype(a.dtype)
+
+
+def compress_forward(y, p, kind, d_comp, eps=1e-5, dt=np.float64, keep=False, store=None):
+    """y [T, m] -> z [T, d_comp].  p: ln_g, ln_b [m] and, for the bottleneck, w_c [d_comp, m].
+
+    `store`: maxout picks one feature per window, a discrete decision taken on floating-point values; a parity
+    test passes the storage type of the kernel under test so that both sides decide on the same numbers (the
+    normalised row rounded to that type).  It only matters for near-ties."""
     y = np.asarray(y, dtype=dt)
     a, xhat, r = layernorm_fwd(y, np.asarray(p["ln_g"], dt), np.asarray(p["ln_b"], dt), eps)
     if kind == "bottleneck":
         z, idx = a @ np.asarray(p["w_c"], dt).T, None
     elif kind == "maxout":
-        z, idx = maxout_fwd(a, y.shape[1] // d_comp)
+        z, idx = maxout_fwd(_stored(a, store), y.shape[1] // d_comp)
     else:
         raise ValueError(kind)
     return (z, dict(a=a, xhat=xhat, r=r, idx=idx)) if keep else z
 
 
-def compress_backward(y, dz, p, grads, kind, d_comp, eps=1e-5, dt=np.float64):
+def compress_backward(y, dz, p, grads, kind, d_comp, eps=1e-5, dt=np.float64, store=None):
     """Recomputes the forward from y; returns dy [T, m] and ADDS the parameter gradients into `grads`."""
-    _, c = compress_forward(y, p, kind, d_comp, eps, dt, keep=True)
+    _, c = compress_forward(y, p, kind, d_comp, eps, dt, keep=True, store=store)
     dz = np.asarray(dz, dtype=dt)
     if kind == "bottleneck":
         grads["w_c"] += dz.T @ c["a"]

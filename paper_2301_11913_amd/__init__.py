@@ -10,4 +10,7 @@ from .binding import (  # noqa: F401
     swarm_codec_encode, swarm_codec_decode, swarm_status_string,
     swarm_stage_coded_workspace_bytes, swarm_stage_forward_coded, swarm_stage_backward_coded,
     PARAM_FIELDS, EXPORTED_SYMBOLS,
+    SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT, BoundaryConfig,
+    swarm_boundary_workspace_bytes, swarm_compress_forward, swarm_compress_backward,
+    swarm_decompress_forward, swarm_decompress_backward,
 )

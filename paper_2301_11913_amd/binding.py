@@ -13,7 +13,10 @@ PARAM_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                 "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm_stage_backward",
                     "swarm_codec_encode", "swarm_codec_decode", "swarm_status_string",
-                    "swarm_stage_coded_workspace_bytes", "swarm_stage_forward_coded", "swarm_stage_backward_coded")
+                    "swarm_stage_coded_workspace_bytes", "swarm_stage_forward_coded", "swarm_stage_backward_coded",
+                    "swarm_boundary_workspace_bytes", "swarm_compress_forward", "swarm_compress_backward",
+                    "swarm_decompress_forward", "swarm_decompress_backward")
+SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 
@@ -32,6 +35,28 @@ class _Config(C.Structure):
 
 class _BlockPtrs(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in PARAM_FIELDS]
+
+
+class _BoundaryConfig(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("d_comp", C.c_int32), ("kind", C.c_int32), ("tokens", C.c_int32),
+                ("dtype", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class _Ptrs3(C.Structure):       # swarm_compress_params / _grads and swarm_decompress_params / _grads
+    _fields_ = [("ln_g", C.c_void_p), ("ln_b", C.c_void_p), ("w", C.c_void_p)]
+
+
+class BoundaryConfig:
+    """Host-side description of a compressed stage boundary (mirrors swarm_boundary_config)."""
+
+    def __init__(self, d_model, d_comp, kind, tokens, dtype, ln_eps=1e-5):
+        if isinstance(kind, str):
+            kind = {"bottleneck": SWARM_COMPRESS_BOTTLENECK, "maxout": SWARM_COMPRESS_MAXOUT}[kind]
+        if isinstance(dtype, str):
+            dtype = {"f32": SWARM_F32, "bf16": SWARM_BF16}[dtype]
+        elif isinstance(dtype, torch.dtype):
+            dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
+        self.c = _BoundaryConfig(d_model, d_comp, kind, tokens, dtype, ln_eps)
 
 
 class StageConfig:
@@ -92,6 +117,18 @@ def load_library():
     lib.swarm_stage_backward_coded.restype = C.c_int
     lib.swarm_stage_backward_coded.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs)] + [C.c_void_p] * 5 + \
                                               [C.POINTER(_BlockPtrs), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_boundary_workspace_bytes.restype = C.c_size_t
+    lib.swarm_boundary_workspace_bytes.argtypes = [C.POINTER(_BoundaryConfig), C.c_int, C.c_int]
+    for name in ("swarm_compress_forward", "swarm_decompress_forward"):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [C.POINTER(_BoundaryConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                       C.c_void_p]
+    for name in ("swarm_compress_backward", "swarm_decompress_backward"):
+        fn = getattr(lib, name)
+        fn.restype = C.c_int
+        fn.argtypes = [C.POINTER(_BoundaryConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p, C.c_void_p,
+                       C.POINTER(_Ptrs3), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -206,3 +243,57 @@ def swarm_stage_backward_coded(cfg: StageConfig, params: List[Dict[str, torch.Te
                                                    workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_stage_backward_coded")
+
+
+def _ptrs3(d: Dict[str, torch.Tensor], wkey: str):
+    return _Ptrs3(_ptr(d["ln_g"]), _ptr(d["ln_b"]), _ptr(d.get(wkey)))
+
+
+def _check_f32(grads: Dict[str, torch.Tensor]):
+    for g in grads.values():
+        if g is not None and g.dtype != torch.float32:
+            raise TypeError("parameter gradients must be fp32")
+
+
+def swarm_boundary_workspace_bytes(cfg: BoundaryConfig, decompress: bool, for_backward: bool) -> int:
+    return int(load_library().swarm_boundary_workspace_bytes(C.byref(cfg.c), int(decompress), int(for_backward)))
+
+
+def swarm_compress_forward(cfg: BoundaryConfig, params: Dict[str, torch.Tensor], y: torch.Tensor, z: torch.Tensor,
+                           workspace: torch.Tensor, stream=None) -> None:
+    st = load_library().swarm_compress_forward(C.byref(cfg.c), C.byref(_ptrs3(params, "w_c")), _ptr(y), _ptr(z),
+                                               _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                               _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_compress_forward")
+
+
+def swarm_compress_backward(cfg: BoundaryConfig, params: Dict[str, torch.Tensor], y: torch.Tensor, dz: torch.Tensor,
+                            dy: torch.Tensor, grads: Dict[str, torch.Tensor], workspace: torch.Tensor,
+                            stream=None) -> None:
+    _check_f32(grads)
+    st = load_library().swarm_compress_backward(C.byref(cfg.c), C.byref(_ptrs3(params, "w_c")), _ptr(y), _ptr(dz),
+                                                _ptr(dy), C.byref(_ptrs3(grads, "w_c")), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_compress_backward")
+
+
+def swarm_decompress_forward(cfg: BoundaryConfig, params: Dict[str, torch.Tensor], z: torch.Tensor, x: torch.Tensor,
+                             workspace: torch.Tensor, stream=None) -> None:
+    st = load_library().swarm_decompress_forward(C.byref(cfg.c), C.byref(_ptrs3(params, "w_d")), _ptr(z), _ptr(x),
+                                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                 _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_decompress_forward")
+
+
+def swarm_decompress_backward(cfg: BoundaryConfig, params: Dict[str, torch.Tensor], z: torch.Tensor, dx: torch.Tensor,
+                              dz: torch.Tensor, grads: Dict[str, torch.Tensor], workspace: torch.Tensor,
+                              stream=None) -> None:
+    _check_f32(grads)
+    st = load_library().swarm_decompress_backward(C.byref(cfg.c), C.byref(_ptrs3(params, "w_d")), _ptr(z), _ptr(dx),
+                                                  _ptr(dz), C.byref(_ptrs3(grads, "w_d")), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_decompress_backward")

@@ -215,8 +215,8 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
       for (int it = 0; it < NITQ; ++it) {
         const int c = lane + it * 64;
         if (c < cq) {
-          float res[8], o[8], xv[8], dv[8], g[8];
-          V8<T>::load(dres + (size_t)row * d + (size_t)(cbase + c) * 8, res);
+          float res[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, o[8], xv[8], dv[8], g[8];
+          if (dres) V8<T>::load(dres + (size_t)row * d + (size_t)(cbase + c) * 8, res);
           V8<T>::unpack(xraw[r][it], xv);
           V8<T>::unpack(dyraw[r][it], dv);
           V8<T>::unpack(graw[it], g);

@@ -54,7 +54,7 @@ swarm_status gemm_generic(const GemmArgs& g, bool bf16, hipStream_t st);
 // y = (x - mean) * rstd * gamma + beta over the last dim d; mean, rstd [T] fp32 are written.
 swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
                            int T, int d, float eps, bool bf16, hipStream_t st);
-// dx = dres + LN-backward(dy), dgamma += sum_t dy*xhat, dbeta += sum_t dy.
+// dx = dres + LN-backward(dy) (dres == nullptr: no residual), dgamma += sum_t dy*xhat, dbeta += sum_t dy.
 // `partial` is scratch of layernorm_bwd_scratch_floats(T, d) floats.
 size_t layernorm_bwd_scratch_floats(int T, int d);
 // With codes != nullptr dx is not stored: its int8 blockwise encoding is (fused stage-exit encode, d % 256 == 0).
@@ -86,6 +86,12 @@ swarm_status rope_apply(void* qkv, const float* table, int T, int S, int d, int 
 swarm_status geglu_fwd(const void* u, void* g, int T, int f, bool bf16, hipStream_t st);
 // du [T,2f] = dg * up * gelu'(gate) | dg * gelu(gate).
 swarm_status geglu_bwd(const void* dg, const void* u, void* du, int T, int f, bool bf16, hipStream_t st);
+
+// ------------------------------------------------------------------ maxout
+// z[t, j] = max_{i<k} a[t, j*k + i]  (a [T, n*k] -> z [T, n]).
+swarm_status maxout_fwd(const void* a, void* z, int T, int n, int k, bool bf16, hipStream_t st);
+// da[t, j*k + i] = dz[t, j] for the first i with a[t, j*k+i] == max of the window, else 0.
+swarm_status maxout_bwd(const void* a, const void* dz, void* da, int T, int n, int k, bool bf16, hipStream_t st);
 
 // ------------------------------------------------------------------ attention
 // qkv [T,3d] (q | k | v along the last dim; head h = columns h*dh..), causal, scores scaled by 1/sqrt(dh).

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _header_symbols():
-    text = open(os.path.join(ROOT, "include", "swarm_stage.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(swarm_[a-z_]+)\s*\(", text)))
 
@@ -87,3 +88,23 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         binding.load_library()
     monkeypatch.delenv("SWARM_STAGE_LIB")
     monkeypatch.setattr(binding, "_lib", None)
+
+
+def test_boundary_layer_validation_without_gpu(lib):
+    ok = sw.BoundaryConfig(256, 128, "bottleneck", 64, "f32")
+    assert sw.swarm_boundary_workspace_bytes(ok, False, False) > 0
+    assert sw.swarm_boundary_workspace_bytes(ok, False, True) > sw.swarm_boundary_workspace_bytes(ok, False, False)
+    assert sw.swarm_boundary_workspace_bytes(ok, True, True) > 0
+    for bad in (sw.BoundaryConfig(250, 128, "bottleneck", 64, "f32"),     # d_model % 64
+                sw.BoundaryConfig(256, 100, "bottleneck", 64, "f32"),     # d_comp % 32
+                sw.BoundaryConfig(256, 512, "bottleneck", 64, "f32"),     # c > m
+                sw.BoundaryConfig(256, 96, "maxout", 64, "f32"),          # m % c for maxout
+                sw.BoundaryConfig(256, 128, "bottleneck", 0, "f32"),
+                sw.BoundaryConfig(256, 128, "bottleneck", 64, "f32", ln_eps=0.0)):
+        assert sw.swarm_boundary_workspace_bytes(bad, False, False) == 0
+    # null pointers are refused before anything touches a device
+    null3 = binding._Ptrs3(None, None, None)
+    st = lib.swarm_compress_forward(C.byref(ok.c), C.byref(null3), None, None, None, 0, None)
+    assert st == -1
+    st = lib.swarm_decompress_backward(C.byref(ok.c), C.byref(null3), None, None, None, C.byref(null3), None, 0, None)
+    assert st == -1
