@@ -73,6 +73,89 @@ def cpu_baseline(wl):
                       % (seq, apps, " + codec" if wl.boundary_codec else "", dt)}
 
 
+def bench_boundary(args):
+    """Workloads of the compression-aware boundary layers: one step = sender forward + backward and receiver
+    forward + backward on one microbatch (both halves of a boundary, as the two neighbouring stages run them)."""
+    import numpy as np
+    import torch
+    import swarm_synth as synth
+    import paper_2301_11913_amd as sw
+    wl = synth.BOUNDARY_WORKLOADS[args.workload]
+    lib = sw.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+    rn = lambda shape, std, mean=0.0: (torch.randn(shape, generator=g, device=dev, dtype=torch.float32) * std + mean).to(dt)
+    T, m, c = wl.tokens, wl.d_model, wl.d_comp
+    comp = {"ln_g": rn((m,), 0.02, 1.0), "ln_b": rn((m,), 0.02)}
+    if wl.kind == "bottleneck":
+        comp["w_c"] = rn((c, m), 0.02)
+    dec = {"ln_g": rn((c,), 0.02, 1.0), "ln_b": rn((c,), 0.02), "w_d": rn((m, c), 0.02)}
+    gc = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in comp.items()}
+    gd = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in dec.items()}
+    y, dx = rn((T, m), 1.0), rn((T, m), wl.grad_sigma)
+    z, dz, x, dy = (torch.empty(s, dtype=dt, device=dev) for s in ((T, c), (T, c), (T, m), (T, m)))
+    cfg = sw.BoundaryConfig(m, c, wl.kind, T, wl.dtype, wl.ln_eps)
+    ws = torch.empty(max(sw.swarm_boundary_workspace_bytes(cfg, d, b) for d in (False, True) for b in (False, True)),
+                     dtype=torch.uint8, device=dev)
+
+    def step():
+        sw.swarm_compress_forward(cfg, comp, y, z, ws)            # sending stage
+        sw.swarm_decompress_forward(cfg, dec, z, x, ws)           # receiving stage
+        sw.swarm_decompress_backward(cfg, dec, z, dx, dz, gd, ws)
+        sw.swarm_compress_backward(cfg, comp, y, dz, dy, gc, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    lib.swarm_kernel_timing_enable.restype = C.c_int
+    lib.swarm_kernel_timing_collect.restype = C.c_int
+    lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    tot_ms, tot_fl, launches = 0.0, 0.0, 0
+    for _ in range(args.steps):
+        lib.swarm_kernel_timing_enable(1)
+        step()
+        ms, fl = C.c_double(), C.c_double()
+        nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
+        tot_ms += ms.value; tot_fl += fl.value; launches += nl
+    lib.swarm_kernel_timing_enable(0)
+    achieved = tot_fl / (tot_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
+                "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
+                "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+    out = {"metric": "boundary layer fwd+bwd tokens/s (sender + receiver halves)",
+           "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+           "config": {"workload": wl.name, "kind": wl.kind, "d_model": m, "d_comp": c, "tokens": T},
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        from oracle import boundary as ob
+        sample = wl.replace(tokens=min(T, 2048))
+        cp, dp = synth.make_boundary_params(sample)
+        ys, dzs, zs, dxs = synth.make_boundary_inputs(sample)
+        t0 = time.perf_counter()
+        zz = ob.compress_forward(ys, cp, wl.kind, c, wl.ln_eps)
+        ob.decompress_forward(zz, dp, wl.ln_eps)
+        dzz = ob.decompress_backward(zz, dxs, dp, {k: np.zeros(v.shape) for k, v in dp.items()}, wl.ln_eps)
+        ob.compress_backward(ys, dzz, cp, {k: np.zeros(v.shape) for k, v in cp.items()}, wl.kind, c, wl.ln_eps)
+        dts = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": torch.get_num_threads(),
+                               "kind": "oracle", "sample": "fp64 numpy oracle, %d tokens through both halves "
+                               "(fwd + recomputing bwd), %.1f s" % (sample.tokens, dts)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +177,8 @@ def main():
     import swarm_synth as synth
     import paper_2301_11913_amd as sw
 
+    if args.workload in synth.BOUNDARY_WORKLOADS:
+        return bench_boundary(args)
     wl = synth.WORKLOADS[args.workload]
     lib = sw.load_library()
     dev = torch.device("cuda:0")
