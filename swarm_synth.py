@@ -20,6 +20,7 @@ hold exactly representable bf16 values, so both sides start from the same bits.
 from __future__ import annotations
 
 import dataclasses
+import math
 import zlib
 
 import numpy as np
@@ -193,3 +194,53 @@ def make_boundary_inputs(wl: BoundaryWorkload):
     T, m, c = wl.tokens, wl.d_model, wl.d_comp
     return (normal(wl.seed, "y", (T, m), 0.0, 1.0, bf), normal(wl.seed, "dz", (T, c), 0.0, wl.grad_sigma, bf),
             normal(wl.seed, "z", (T, c), 0.0, 1.0, bf), normal(wl.seed, "dx", (T, m), 0.0, wl.grad_sigma, bf))
+
+
+# ----------------------------------------------------------------------------------------------------
+# First / last stage extras (Section 4.3): token embedding and language-modelling head + loss.
+@dataclasses.dataclass(frozen=True)
+class HeadWorkload:
+    name: str
+    dtype: str
+    d_model: int
+    vocab: int            # V: number of real tokens
+    vocab_rows: int       # rows of the weight matrices (V padded to a tile multiple; rows >= V are padding)
+    tokens: int           # T = microbatch * sequence
+    ln_eps: float = 1e-5
+    seed: int = BASE_SEED + 200
+
+    def replace(self, **kw) -> "HeadWorkload":
+        return dataclasses.replace(self, **kw)
+
+
+HEAD_WORKLOADS = {
+    # the Section 4.3 model: d_model 4096, the GPT-2 tokenizer's 50257 tokens, one 2048-token sequence per microbatch
+    "head_gpt2vocab_bf16_d4096": HeadWorkload("head_gpt2vocab_bf16_d4096", "bf16", 4096, 50257, 50432, 2048,
+                                              seed=BASE_SEED + 201),
+}
+
+
+def make_head_params(wl: HeadWorkload):
+    """(embedding table [rows, d], head params ln_g, ln_b [d], w_vocab [rows, d]); padding rows are zero."""
+    bf = wl.dtype == "bf16"
+    d = wl.d_model
+    table = normal(wl.seed, "table", (wl.vocab_rows, d), 0.0, 0.02, bf)
+    w = normal(wl.seed, "w_vocab", (wl.vocab_rows, d), 0.0, 0.02, bf)
+    table[wl.vocab:] = 0.0
+    w[wl.vocab:] = 0.0
+    head = {"ln_g": normal(wl.seed, "h.ln_g", (d,), 1.0, 0.02, bf), "ln_b": normal(wl.seed, "h.ln_b", (d,), 0.0, 0.02, bf),
+            "w_vocab": w}
+    return table, head
+
+
+def make_head_inputs(wl: HeadWorkload):
+    """tokens [T] and targets [T] (int32, Zipf-like: frequent ids repeat inside a microbatch, as in text),
+    x [T, d] (input of the head), dx_emb [T, d] (gradient arriving at the embedding)."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(_tensor_seed(wl.seed, "tokens"))
+    u = torch.rand((2, wl.tokens), generator=g, dtype=torch.float64)
+    ids = torch.floor(torch.exp(u * math.log(wl.vocab))).to(torch.int64).clamp_(1, wl.vocab) - 1   # log-uniform ranks
+    bf = wl.dtype == "bf16"
+    return (ids[0].to(torch.int32).numpy(), ids[1].to(torch.int32).numpy(),
+            normal(wl.seed, "x", (wl.tokens, wl.d_model), 0.0, 1.0, bf),
+            normal(wl.seed, "dx_emb", (wl.tokens, wl.d_model), 0.0, 1e-2, bf))
