@@ -13,4 +13,6 @@ from .binding import (  # noqa: F401
     SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT, BoundaryConfig,
     swarm_boundary_workspace_bytes, swarm_compress_forward, swarm_compress_backward,
     swarm_decompress_forward, swarm_decompress_backward,
+    HeadConfig, swarm_embedding_forward, swarm_embedding_backward, swarm_head_workspace_bytes,
+    swarm_head_loss, swarm_head_loss_backward,
 )

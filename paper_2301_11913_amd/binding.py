@@ -15,7 +15,9 @@ EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm
                     "swarm_codec_encode", "swarm_codec_decode", "swarm_status_string",
                     "swarm_stage_coded_workspace_bytes", "swarm_stage_forward_coded", "swarm_stage_backward_coded",
                     "swarm_boundary_workspace_bytes", "swarm_compress_forward", "swarm_compress_backward",
-                    "swarm_decompress_forward", "swarm_decompress_backward")
+                    "swarm_decompress_forward", "swarm_decompress_backward",
+                    "swarm_embedding_forward", "swarm_embedding_backward", "swarm_head_workspace_bytes",
+                    "swarm_head_loss", "swarm_head_loss_backward")
 SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -57,6 +59,22 @@ class BoundaryConfig:
         elif isinstance(dtype, torch.dtype):
             dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
         self.c = _BoundaryConfig(d_model, d_comp, kind, tokens, dtype, ln_eps)
+
+
+class _HeadConfig(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("vocab", C.c_int32), ("vocab_rows", C.c_int32), ("tokens", C.c_int32),
+                ("dtype", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class HeadConfig:
+    """Host-side description of the language-modelling head (mirrors swarm_head_config)."""
+
+    def __init__(self, d_model, vocab, vocab_rows, tokens, dtype, ln_eps=1e-5):
+        if isinstance(dtype, str):
+            dtype = {"f32": SWARM_F32, "bf16": SWARM_BF16}[dtype]
+        elif isinstance(dtype, torch.dtype):
+            dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
+        self.c = _HeadConfig(d_model, vocab, vocab_rows, tokens, dtype, ln_eps)
 
 
 class StageConfig:
@@ -129,6 +147,21 @@ def load_library():
         fn.restype = C.c_int
         fn.argtypes = [C.POINTER(_BoundaryConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p, C.c_void_p,
                        C.POINTER(_Ptrs3), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_embedding_forward.restype = C.c_int
+    lib.swarm_embedding_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p]
+    lib.swarm_embedding_backward.restype = C.c_int
+    lib.swarm_embedding_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p]
+    lib.swarm_head_workspace_bytes.restype = C.c_size_t
+    lib.swarm_head_workspace_bytes.argtypes = [C.POINTER(_HeadConfig), C.c_int]
+    lib.swarm_head_loss.restype = C.c_int
+    lib.swarm_head_loss.argtypes = [C.POINTER(_HeadConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_head_loss_backward.restype = C.c_int
+    lib.swarm_head_loss_backward.argtypes = [C.POINTER(_HeadConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_Ptrs3), C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -297,3 +330,53 @@ def swarm_decompress_backward(cfg: BoundaryConfig, params: Dict[str, torch.Tenso
                                                   workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_decompress_backward")
+
+
+def swarm_embedding_forward(tokens: torch.Tensor, table: torch.Tensor, vocab: int, x: torch.Tensor,
+                            stream=None) -> None:
+    if tokens.dtype != torch.int32:
+        raise TypeError("token ids must be int32")
+    st = load_library().swarm_embedding_forward(_ptr(tokens), _ptr(table), _dtype_code(table), tokens.numel(), vocab,
+                                                table.shape[1], _ptr(x), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_embedding_forward")
+
+
+def swarm_embedding_backward(tokens: torch.Tensor, dx: torch.Tensor, vocab: int, grad_table: torch.Tensor,
+                             stream=None) -> None:
+    if tokens.dtype != torch.int32 or grad_table.dtype != torch.float32:
+        raise TypeError("token ids must be int32 and grad_table fp32")
+    st = load_library().swarm_embedding_backward(_ptr(tokens), _ptr(dx), _dtype_code(dx), tokens.numel(), vocab,
+                                                 dx.shape[1], _ptr(grad_table), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_embedding_backward")
+
+
+def swarm_head_workspace_bytes(cfg: HeadConfig, for_backward: bool) -> int:
+    return int(load_library().swarm_head_workspace_bytes(C.byref(cfg.c), int(for_backward)))
+
+
+def swarm_head_loss(cfg: HeadConfig, params: Dict[str, torch.Tensor], x: torch.Tensor, targets: torch.Tensor,
+                    loss: torch.Tensor, token_loss: Optional[torch.Tensor], workspace: torch.Tensor,
+                    stream=None) -> None:
+    if targets.dtype != torch.int32 or loss.dtype != torch.float32:
+        raise TypeError("targets must be int32 and loss fp32")
+    st = load_library().swarm_head_loss(C.byref(cfg.c), C.byref(_ptrs3(params, "w_vocab")), _ptr(x), _ptr(targets),
+                                        _ptr(loss), _ptr(token_loss), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_head_loss")
+
+
+def swarm_head_loss_backward(cfg: HeadConfig, params: Dict[str, torch.Tensor], x: torch.Tensor, targets: torch.Tensor,
+                             loss: torch.Tensor, token_loss: Optional[torch.Tensor], dx: torch.Tensor,
+                             grads: Dict[str, torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
+    if targets.dtype != torch.int32 or loss.dtype != torch.float32:
+        raise TypeError("targets must be int32 and loss fp32")
+    _check_f32(grads)
+    st = load_library().swarm_head_loss_backward(C.byref(cfg.c), C.byref(_ptrs3(params, "w_vocab")), _ptr(x),
+                                                 _ptr(targets), _ptr(loss), _ptr(token_loss), _ptr(dx),
+                                                 C.byref(_ptrs3(grads, "w_vocab")), _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_head_loss_backward")

@@ -108,3 +108,21 @@ def test_boundary_layer_validation_without_gpu(lib):
     assert st == -1
     st = lib.swarm_decompress_backward(C.byref(ok.c), C.byref(null3), None, None, None, C.byref(null3), None, 0, None)
     assert st == -1
+
+
+def test_head_validation_without_gpu(lib):
+    ok = sw.HeadConfig(256, 1000, 1024, 64, "f32")
+    assert sw.swarm_head_workspace_bytes(ok, True) > sw.swarm_head_workspace_bytes(ok, False) > 0
+    for bad in (sw.HeadConfig(250, 1000, 1024, 64, "f32"),      # d_model % 64
+                sw.HeadConfig(256, 1000, 999, 64, "f32"),       # fewer rows than tokens in the vocabulary
+                sw.HeadConfig(256, 1000, 1004, 64, "f32"),      # rows % 8
+                sw.HeadConfig(256, 0, 1024, 64, "f32"),
+                sw.HeadConfig(256, 1000, 1024, 0, "f32")):
+        assert sw.swarm_head_workspace_bytes(bad, False) == 0
+    null3 = binding._Ptrs3(None, None, None)
+    assert lib.swarm_head_loss(C.byref(ok.c), C.byref(null3), None, None, None, None, None, 0, None) == -1
+    assert lib.swarm_embedding_forward(None, None, 0, 4, 10, 64, None, None) == -1
+    # shape errors come before any launch: the pointers below are never dereferenced
+    dummy = C.c_void_p(256)
+    assert lib.swarm_embedding_backward(dummy, dummy, 1, 70000, 10, 64, dummy, None) == -2   # T > 65536
+    assert lib.swarm_embedding_forward(dummy, dummy, 1, 4, 10, 60, dummy, None) == -2        # d % 8
