@@ -156,6 +156,89 @@ def bench_boundary(args):
     print(json.dumps(out))
 
 
+def bench_head(args):
+    """Workload of the first / last stage extras: one step = embedding forward + backward (first stage) and
+    head loss + backward (last stage) on one microbatch."""
+    import numpy as np
+    import torch
+    import swarm_synth as synth
+    import paper_2301_11913_amd as sw
+    wl = synth.HEAD_WORKLOADS[args.workload]
+    lib = sw.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+    rn = lambda shape, std, mean=0.0: (torch.randn(shape, generator=g, device=dev, dtype=torch.float32) * std + mean).to(dt)
+    T, d, V, Vp = wl.tokens, wl.d_model, wl.vocab, wl.vocab_rows
+    table, w = rn((Vp, d), 0.02), rn((Vp, d), 0.02)
+    table[V:] = 0; w[V:] = 0
+    head = {"ln_g": rn((d,), 0.02, 1.0), "ln_b": rn((d,), 0.02), "w_vocab": w}
+    grads = {k: torch.zeros(v.shape, dtype=torch.float32, device=dev) for k, v in head.items()}
+    grad_table = torch.zeros((Vp, d), dtype=torch.float32, device=dev)
+    tok_np, tgt_np, _, _ = synth.make_head_inputs(wl.replace(d_model=8))      # ids only (log-uniform ranks)
+    tokens, targets = torch.from_numpy(tok_np).to(dev), torch.from_numpy(tgt_np).to(dev)
+    x_emb = torch.empty((T, d), dtype=dt, device=dev)
+    x_head, dx_emb = rn((T, d), 1.0), rn((T, d), 1e-2)
+    dx_head = torch.empty((T, d), dtype=dt, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    cfg = sw.HeadConfig(d, V, Vp, T, wl.dtype, wl.ln_eps)
+    ws = torch.empty(sw.swarm_head_workspace_bytes(cfg, True), dtype=torch.uint8, device=dev)
+
+    def step():
+        sw.swarm_embedding_forward(tokens, table, V, x_emb)                               # first stage
+        sw.swarm_head_loss_backward(cfg, head, x_head, targets, loss, None, dx_head, grads, ws)   # last stage
+        sw.swarm_embedding_backward(tokens, dx_emb, V, grad_table)                        # first stage
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    lib.swarm_kernel_timing_enable.restype = C.c_int
+    lib.swarm_kernel_timing_collect.restype = C.c_int
+    lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    tot_ms, tot_fl, launches = 0.0, 0.0, 0
+    for _ in range(args.steps):
+        lib.swarm_kernel_timing_enable(1)
+        step()
+        ms, fl = C.c_double(), C.c_double()
+        nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
+        tot_ms += ms.value; tot_fl += fl.value; launches += nl
+    lib.swarm_kernel_timing_enable(0)
+    achieved = tot_fl / (tot_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
+                "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
+                "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+    out = {"metric": "embedding fwd+bwd and LM head loss+bwd tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
+           "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": wl.dtype, "data": "synthetic",
+           "config": {"workload": wl.name, "d_model": d, "vocab": V, "vocab_rows": Vp, "tokens": T},
+           "loss": round(float(loss.item()), 4), "roofline": roofline}
+    if not args.no_cpu_baseline:
+        from oracle import head as oh
+        sample = wl.replace(tokens=min(T, 256))
+        tab, hp = synth.make_head_params(sample)
+        tk, tg, xs, dxe = synth.make_head_inputs(sample)
+        t0 = time.perf_counter()
+        oh.embedding_forward(tk, tab)
+        oh.head_loss_backward(xs, tg, hp, V, {k: np.zeros(v.shape) for k, v in hp.items()}, wl.ln_eps)
+        oh.embedding_backward(tk, dxe, np.zeros(tab.shape))
+        dts = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": torch.get_num_threads(),
+                               "kind": "oracle", "sample": "fp64 numpy oracle, %d tokens (embedding fwd + bwd, head "
+                               "loss + bwd), %.1f s" % (sample.tokens, dts)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,6 +262,8 @@ def main():
 
     if args.workload in synth.BOUNDARY_WORKLOADS:
         return bench_boundary(args)
+    if args.workload in synth.HEAD_WORKLOADS:
+        return bench_head(args)
     wl = synth.WORKLOADS[args.workload]
     lib = sw.load_library()
     dev = torch.device("cuda:0")
