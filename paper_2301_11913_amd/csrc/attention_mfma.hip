@@ -184,16 +184,20 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Causal rows get longer with the query index: a workgroup takes query tile nqt-1-pi and then tile pi, so every
+  // workgroup does the same amount of work and the launch has no tail of long rows.
   const int nqt = (S + 127) / 128;
-  int qi, h, b;
-  tile_head_batch(nqt, H, qi, h, b);
-  const int qt = nqt - 1 - qi;          // longest rows first
+  int pi, h, b;
+  tile_head_batch((nqt + 1) / 2, H, pi, h, b);
   const int d = H * DH, ld = 3 * d;
-  const int q0 = qt * 128;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
   const bf16_raw* K = Q + d;
   const bf16_raw* V = Q + 2 * d;
   const float c = kLog2e / sqrtf((float)DH);
+  for (int pass = 0; pass < 2; ++pass) {
+  const int qt = pass == 0 ? nqt - 1 - pi : pi;
+  if (pass == 1 && qt == nqt - 1 - pi) break;     // odd tile count: the middle tile has no partner
+  const int q0 = qt * 128;
 
   const int qrow = q0 + 32 * w + l32;
   bf16x8 qf[KS];
@@ -313,6 +317,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
     store_rowT<DB>(o + ((size_t)b * S + qrow) * d + h * DH, oacc, 1.0f / l, lg);
     if (lg == 0) lse[((size_t)b * H + h) * S + qrow] = m * (c / kLog2e) + logf(l);
   }
+  }   // pass
 }
 
 // ---- backward -----------------------------------------------------------------------------------
@@ -360,8 +365,13 @@ __global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_
   const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int w = w8 & 3;
   const bool is_dk = w8 >= 4;
-  int kb, h, b;
-  tile_head_batch((S + 127) / 128, H, kb, h, b);
+  // key block pi (the longest sweep over the query tiles), then its partner nkb-1-pi: equal work per workgroup
+  const int nkb = (S + 127) / 128;
+  int pi, h, b;
+  tile_head_batch((nkb + 1) / 2, H, pi, h, b);
+  for (int pass = 0; pass < 2; ++pass) {
+  const int kb = pass == 0 ? pi : nkb - 1 - pi;
+  if (pass == 1 && kb == pi) break;
   const int d = H * DH, ld = 3 * d;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
   const bf16_raw* K = Q + d;
@@ -491,6 +501,7 @@ __global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_
     if (is_dk) store_rowT<DB>(dkrow, acc, scale, lg);
     else store_rowT<DB>(dkrow + d, acc, 1.0f, lg);
   }
+  }   // pass
 }
 
 // dQ: grid (ceil(S/128), H, B); wavefront w owns query rows q0+32w..+31; KV tiles of 64.
@@ -507,10 +518,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, lg = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nqt = (S + 127) / 128;
-  int qi, h, b;
-  tile_head_batch(nqt, H, qi, h, b);
-  const int qtile = nqt - 1 - qi;       // longest rows first
+  int pi, h, b;
+  tile_head_batch((nqt + 1) / 2, H, pi, h, b);
   const int d = H * DH, ld = 3 * d;
+  for (int pass = 0; pass < 2; ++pass) {          // query tile nqt-1-pi, then its partner pi (equal work per workgroup)
+  const int qtile = pass == 0 ? nqt - 1 - pi : pi;
+  if (pass == 1 && qtile == nqt - 1 - pi) break;
   const int q0 = qtile * 128;
   const bf16_raw* Q = qkv + (size_t)b * S * ld + h * DH;
   const bf16_raw* K = Q + d;
@@ -607,6 +620,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
   }
 
   if (qrow < S) store_rowT<DB>(dqkv + ((size_t)b * S + qrow) * ld + h * DH, dqacc, scale, lg);
+  }   // pass
 }
 
 template <typename Kern>
@@ -624,8 +638,8 @@ swarm_status launch_fwd(const bf16_raw* qkv, bf16_raw* o, float* lse, int B, int
   constexpr size_t lds_bytes = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
   static bool a0 = false;
   if (set_lds(attn_fwd_kernel<DH>, lds_bytes, a0) != SWARM_OK) return SWARM_ERR_LAUNCH;
-  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3(((S + 127) / 128) * H * B), dim3(kThreads), lds_bytes, st, qkv, o,
-                     lse, S, H);
+  hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((((S + 127) / 128 + 1) / 2) * H * B), dim3(kThreads), lds_bytes, st,
+                     qkv, o, lse, S, H);
   return launch_status();
 }
 
@@ -638,7 +652,7 @@ swarm_status launch_bwd(const bf16_raw* qkv, const bf16_raw* o, const bf16_raw* 
   if (set_lds(attn_bwd_dkdv_kernel<DH>, lds_dkdv, a1) != SWARM_OK) return SWARM_ERR_LAUNCH;
   if (set_lds(attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3(B * S), dim3(kThreads), 0, st, o, dout, delta, S, H);
-  dim3 grid(((S + 127) / 128) * H * B);
+  dim3 grid((((S + 127) / 128 + 1) / 2) * H * B);   // workgroups take pairs of tiles
   hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, grid, dim3(kDkDvThreads), lds_dkdv, st, qkv, dout, lse, delta, dqkv, S,
                      H);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DH>, grid, dim3(kThreads), lds_dq, st, qkv, dout, lse, delta, dqkv, S, H);
