@@ -15,6 +15,33 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// 8 consecutive elements <-> fp32
+template <typename T> __device__ __forceinline__ void ld8(const T* p, float (&x)[8]);
+template <> __device__ __forceinline__ void ld8<bf16_raw>(const bf16_raw* p, float (&x)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __uint_as_float(w[i] << 16);
+    x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+template <> __device__ __forceinline__ void ld8<float>(const float* p, float (&x)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+template <typename T> __device__ __forceinline__ void st8(T* p, const float (&x)[8]);
+template <> __device__ __forceinline__ void st8<bf16_raw>(bf16_raw* p, const float (&x)[8]) {
+  uint4 v;
+  v.x = pack_bf16x2(x[0], x[1]); v.y = pack_bf16x2(x[2], x[3]);
+  v.z = pack_bf16x2(x[4], x[5]); v.w = pack_bf16x2(x[6], x[7]);
+  *reinterpret_cast<uint4*>(p) = v;
+}
+template <> __device__ __forceinline__ void st8<float>(float* p, const float (&x)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+}
+
 // ---------------------------------------------------------------------------------------- embedding
 // x[t, :] = table[token[t], :]; one thread moves 16 bytes
 template <typename T>
@@ -83,8 +110,10 @@ __global__ __launch_bounds__(kThreads) void embedding_bwd_kernel(const int32_t* 
       for (int q = 0; q < MAXC; ++q) {
         const int c = threadIdx.x + q * kThreads;
         if (c < nch) {
+          float v[8];
+          ld8<T>(row + c * 8, v);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[q][e] += Elem<T>::load(row + c * 8 + e);
+          for (int e = 0; e < 8; ++e) acc[q][e] += v[e];
         }
       }
     }
@@ -112,10 +141,18 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(T* __restrict__ lo
   __shared__ float s_m[kThreads / 64], s_s[kThreads / 64];
   T* row = logits + (size_t)blockIdx.x * ld;
   float m = -INFINITY, s = 0.f;
-  for (int v = threadIdx.x; v < vocab; v += kThreads) {
-    const float l = Elem<T>::load(row + v);
-    if (l > m) { s *= __expf(m - l); m = l; }
-    s += __expf(l - m);
+  for (int c = threadIdx.x; c * 8 < vocab; c += kThreads) {     // rows are 8-element aligned (ld % 8 == 0)
+    float l[8];
+    ld8<T>(row + c * 8, l);
+    float cm = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (c * 8 + e >= vocab) l[e] = -INFINITY;
+      cm = fmaxf(cm, l[e]);
+    }
+    if (cm > m) { s *= __expf(m - cm); m = cm; }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += __expf(l[e] - m);          // exp(-inf) = 0 for the padding
   }
   // combine (m, s) pairs: lanes, then wavefronts, in a fixed order
 #pragma unroll
@@ -142,10 +179,15 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(T* __restrict__ lo
   if (threadIdx.x == 0) token_loss[blockIdx.x] = lse - (tgt_ok ? Elem<T>::load(row + tgt) : 0.f);
   if constexpr (GRAD) {
     __syncthreads();             // the target logit has been read before the row is overwritten
-    for (int v = threadIdx.x; v < ld; v += kThreads) {
-      float g = 0.f;
-      if (v < vocab) g = (__expf(Elem<T>::load(row + v) - lse) - (v == tgt ? 1.f : 0.f)) * inv_T;
-      Elem<T>::store(row + v, g);
+    for (int c = threadIdx.x; c * 8 < ld; c += kThreads) {
+      float l[8], g[8];
+      ld8<T>(row + c * 8, l);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int v = c * 8 + e;
+        g[e] = v < vocab ? (__expf(l[e] - lse) - (v == tgt ? 1.f : 0.f)) * inv_T : 0.f;
+      }
+      st8<T>(row + c * 8, g);
     }
   }
 }
@@ -277,7 +319,7 @@ extern "C" swarm_status swarm_embedding_backward(const int32_t* tokens, const vo
                                                  void* hip_stream) {
   if (!tokens || !dx || !grad_table) return SWARM_ERR_NULL;
   if (dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
-  if (n_tokens < 1 || n_tokens > 65536 || vocab < 1 || d_model < 8 || d_model % 8 || d_model > 8192)
+  if (n_tokens < 1 || n_tokens > 65536 || vocab < 1 || d_model < 8 || d_model % 8 || d_model > 8192 || !al16(dx))
     return SWARM_ERR_SHAPE;
   hipStream_t st = (hipStream_t)hip_stream;
   if (dtype == SWARM_BF16)
