@@ -105,6 +105,40 @@ struct Tile64 {
     const uint2 a = __builtin_bit_cast(uint2, lo), b = __builtin_bit_cast(uint2, hi);
     return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
   }
+  // Loop-invariant parts of the two reads above, as byte offsets inside a tile: the kernels compute them once
+  // per lane before their tile loops, so that a fragment read costs one address add instead of the swizzle
+  // arithmetic (which otherwise makes these kernels VALU-bound).
+  static __device__ __forceinline__ uint32_t rows_off(int row, int chunk) {
+    return (uint32_t)(row * DH + ((chunk ^ swz<DH>(row)) << 3)) * 2u;
+  }
+  static __device__ __forceinline__ bf16x8 rows_at(const bf16_raw* tile, uint32_t off) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(tile) + off));
+  }
+  // offsets of the two transpose reads of cols(tile, cbase, 0, lane); the swizzle of a row depends on its low four
+  // bits only, so a row base that is a multiple of 16 just adds rbase * DH * 2 bytes (an immediate offset)
+  static __device__ __forceinline__ void cols_off(int cbase, int lane, uint32_t& o0, uint32_t& o1) {
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int col = cbase + 16 * (grp & 1) + 4 * (l16 & 3);
+    const int r0 = 4 * (grp >> 1) + (l16 >> 2);
+    const int r1 = r0 + 8;
+    o0 = (uint32_t)(r0 * DH + (((col >> 3) ^ swz<DH>(r0)) << 3) + (col & 4)) * 2u;
+    o1 = (uint32_t)(r1 * DH + (((col >> 3) ^ swz<DH>(r1)) << 3) + (col & 4)) * 2u;
+  }
+  template <int RB>
+  static __device__ __forceinline__ bf16x8 cols_at_rb(uint32_t base, uint32_t o0, uint32_t o1) {
+    uint2 a, b;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(a) : "v"(base + o0), "n"(RB * DH * 2) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(b) : "v"(base + o1), "n"(RB * DH * 2) : "memory");
+    return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
+  }
+  // cols_raw(tile, cbase, rbase, lane) with rbase in {0, 16, 32, 48} and (o0, o1) = cols_off(cbase, lane)
+  static __device__ __forceinline__ bf16x8 cols_at(const bf16_raw* tile, int rbase, uint32_t o0, uint32_t o1) {
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)tile;
+    if (rbase == 0) return cols_at_rb<0>(base, o0, o1);
+    if (rbase == 16) return cols_at_rb<16>(base, o0, o1);
+    if (rbase == 32) return cols_at_rb<32>(base, o0, o1);
+    return cols_at_rb<48>(base, o0, o1);
+  }
   // The same block, read with plain instructions (two LDS reads).  Behind the compiler's builtin every pending
   // global -> LDS load counts as a possible writer of the bytes read and is waited for (vmcnt(0)), which would
   // serialise the next tile's loads with this tile's reads; the stages are disjoint by construction.  The
@@ -219,6 +253,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
   __builtin_amdgcn_s_barrier();
 
   const int wq_min = q0 + 32 * w, wq_max = wq_min + 31;
+  uint32_t koff[2 * KS], voff[DB][2];      // per-lane tile offsets of the K-row and V^T fragment reads
+#pragma unroll
+  for (int n = 0; n < 2 * KS; ++n) koff[n] = T::rows_off(32 * (n & 1) + l32, 2 * (n >> 1) + lg);
+#pragma unroll
+  for (int i = 0; i < DB; ++i) T::cols_off(32 * i, lane, voff[i][0], voff[i][1]);
   for (int t = 0; t < ntile; ++t) {
     const bf16_raw* sK = lds + (t & 1) * STAGE;
     const bf16_raw* sV = sK + T::ELEMS;
@@ -232,13 +271,13 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
       zero(s);
       bf16x8 kr[RING];
 #pragma unroll
-      for (int n = 0; n < PF; ++n) kr[n] = T::rows(sK, 32 * (n & 1) + l32, 2 * (n >> 1) + lg);
+      for (int n = 0; n < PF; ++n) kr[n] = T::rows_at(sK, koff[n]);
 #pragma unroll
       for (int n = 0; n < NQK; ++n) {
         s[n & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[n % RING], qf[n >> 1], s[n & 1], 0, 0, 0);
         if (n + PF < NQK) {
           const int f = n + PF;
-          kr[f % RING] = T::rows(sK, 32 * (f & 1) + l32, 2 * (f >> 1) + lg);
+          kr[f % RING] = T::rows_at(sK, koff[f]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -247,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
       constexpr int NPV = 4 * DB;
       bf16x8 vr[RING];
 #pragma unroll
-      for (int n = 0; n < PF; ++n) vr[n] = T::cols_raw(sV, 32 * (n % DB), 16 * (n / DB), lane);
+      for (int n = 0; n < PF; ++n) vr[n] = T::cols_at(sV, 16 * (n / DB), voff[n % DB][0], voff[n % DB][1]);
       if (kv0 + 63 > wq_min) {   // tile touches the diagonal (or the sequence end): mask kv > q
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -303,7 +342,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
         oacc[n % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[n % RING], pf[n / DB], oacc[n % DB], 0, 0, 0);
         if (n + PF < NPV) {
           const int f = n + PF;
-          vr[f % RING] = T::cols_raw(sV, 32 * (f % DB), 16 * (f / DB), lane);
+          vr[f % RING] = T::cols_at(sV, 16 * (f / DB), voff[f % DB][0], voff[f % DB][1]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
