@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 
 def measured_traffic(workload):
@@ -239,6 +240,81 @@ def bench_head(args):
     print(json.dumps(out))
 
 
+def bench_lamb(args):
+    """Optimiser workload: one step = one LAMB update of every parameter tensor of a stage."""
+    import numpy as np
+    import torch
+    import swarm_synth as synth
+    import paper_2301_11913_amd as sw
+    wl = synth.LAMB_WORKLOADS[args.workload]
+    sw.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+    sizes = [int(np.prod(s)) for s in wl.shapes]
+    tensors = []
+    for shape, n in zip(wl.shapes, sizes):
+        w = torch.randn(n, generator=g, device=dev) * 0.02 + (1.0 if len(shape) == 1 else 0.0)
+        tensors.append(dict(w=w, p=w.to(dt), g=torch.randn(n, generator=g, device=dev) * 1e-3,
+                            m=torch.zeros(n, device=dev), v=torch.zeros(n, device=dev)))
+    ws = torch.empty(max(sw.swarm_lamb_workspace_bytes(n) for n in sizes), dtype=torch.uint8, device=dev)
+    t_step = [0]
+
+    def step():
+        t_step[0] += 1
+        for t in tensors:
+            sw.swarm_lamb_step(t["w"], t["p"], t["g"], t["m"], t["v"], t_step[0], ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # the largest tensor's update, timed with events on the launch stream (the binding launches on torch's current one)
+    big = max(range(len(sizes)), key=lambda i: sizes[i])
+    t, ev = tensors[big], [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                           for _ in range(args.steps)]
+    for e0, e1 in ev:
+        t_step[0] += 1
+        e0.record()
+        sw.swarm_lamb_step(t["w"], t["p"], t["g"], t["m"], t["v"], t_step[0], ws)
+        e1.record()
+    torch.cuda.synchronize()
+    ms_big = sum(e0.elapsed_time(e1) for e0, e1 in ev) / len(ev)
+    # per element: first pass reads w, g, m, v and writes m, v, u (28 B); update reads w, u, writes w and the copy
+    bytes_per_elem = 28 + 12 + (2 if wl.dtype == "bf16" else 4)
+    achieved = bytes_per_elem * sizes[big] / (ms_big * 1e-3) / 1e9
+    n_total = sum(sizes)
+    out = {"metric": "LAMB parameters updated per second", "value": round(n_total / (ms_per_step * 1e-3), 1),
+           "unit": "parameters/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl.name, "tensors": len(sizes), "parameters": n_total, "param_copy": wl.dtype},
+           "roofline": {"bound": "hbm", "kernel": "lamb_moments_kernel + lamb_ratio_kernel + lamb_apply_kernel",
+                        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
+                        "elements": sizes[big], "bytes_per_element": bytes_per_elem, "avg_update_us": round(ms_big * 1e3, 1)}}
+    if not args.no_cpu_baseline:
+        from oracle.lamb import lamb_step
+        n = 1 << 24
+        w, gr = synth.make_lamb_tensor(wl, big, n)
+        m, v = np.zeros(n), np.zeros(n)
+        t0 = time.perf_counter()
+        for k in range(1, 4):
+            w, m, v, _ = lamb_step(w, gr, m, v, k)
+        dts = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 3 * n / dts, "unit": "parameters/s", "cores": 1, "kind": "oracle",
+                               "sample": "fp64 numpy oracle, 3 steps on the first %d elements of the largest tensor, "
+                                         "%.1f s" % (n, dts)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -264,6 +340,8 @@ def main():
         return bench_boundary(args)
     if args.workload in synth.HEAD_WORKLOADS:
         return bench_head(args)
+    if args.workload in synth.LAMB_WORKLOADS:
+        return bench_lamb(args)
     wl = synth.WORKLOADS[args.workload]
     lib = sw.load_library()
     dev = torch.device("cuda:0")

@@ -2,8 +2,8 @@
 
 Nothing in the product path imports this module; it exists to check the HIP kernels.
 
-The appendix "Additional Details for Section 4.3" trains with LAMB "following the configuration from the original
-paper", with learning rate 1e-3 and beta2 = 0.95.  The update of one parameter tensor w (the trust ratio is taken
+The appendix "Additional Details for Section 4.3" trains with LAMB in the configuration of the optimiser's own
+publication, except for the learning rate (1e-3) and beta2 (0.95).  The update of one parameter tensor w (the trust ratio is taken
 per tensor, "layer-wise"), for the gradient g accumulated over a global batch:
 
     g   = grad_scale * grad

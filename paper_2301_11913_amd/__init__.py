@@ -15,4 +15,5 @@ from .binding import (  # noqa: F401
     swarm_decompress_forward, swarm_decompress_backward,
     HeadConfig, swarm_embedding_forward, swarm_embedding_backward, swarm_head_workspace_bytes,
     swarm_head_loss, swarm_head_loss_backward,
+    swarm_lamb_workspace_bytes, swarm_lamb_step,
 )

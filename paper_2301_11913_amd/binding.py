@@ -17,7 +17,8 @@ EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm
                     "swarm_boundary_workspace_bytes", "swarm_compress_forward", "swarm_compress_backward",
                     "swarm_decompress_forward", "swarm_decompress_backward",
                     "swarm_embedding_forward", "swarm_embedding_backward", "swarm_head_workspace_bytes",
-                    "swarm_head_loss", "swarm_head_loss_backward")
+                    "swarm_head_loss", "swarm_head_loss_backward",
+                    "swarm_lamb_workspace_bytes", "swarm_lamb_step")
 SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -75,6 +76,11 @@ class HeadConfig:
         elif isinstance(dtype, torch.dtype):
             dtype = {torch.float32: SWARM_F32, torch.bfloat16: SWARM_BF16}[dtype]
         self.c = _HeadConfig(d_model, vocab, vocab_rows, tokens, dtype, ln_eps)
+
+
+class _LambConfig(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("grad_scale", C.c_float), ("step", C.c_int32)]
 
 
 class StageConfig:
@@ -162,6 +168,11 @@ def load_library():
     lib.swarm_head_loss_backward.argtypes = [C.POINTER(_HeadConfig), C.POINTER(_Ptrs3), C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(_Ptrs3), C.c_void_p,
                                              C.c_size_t, C.c_void_p]
+    lib.swarm_lamb_workspace_bytes.restype = C.c_size_t
+    lib.swarm_lamb_workspace_bytes.argtypes = [C.c_size_t]
+    lib.swarm_lamb_step.restype = C.c_int
+    lib.swarm_lamb_step.argtypes = [C.POINTER(_LambConfig), C.c_size_t, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -380,3 +391,23 @@ def swarm_head_loss_backward(cfg: HeadConfig, params: Dict[str, torch.Tensor], x
                                                  workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_head_loss_backward")
+
+
+def swarm_lamb_workspace_bytes(n_elems: int) -> int:
+    return int(load_library().swarm_lamb_workspace_bytes(n_elems))
+
+
+def swarm_lamb_step(master: torch.Tensor, param: Optional[torch.Tensor], grad: torch.Tensor, m: torch.Tensor,
+                    v: torch.Tensor, step: int, workspace: torch.Tensor, lr: float = 1e-3, beta1: float = 0.9,
+                    beta2: float = 0.95, eps: float = 1e-6, weight_decay: float = 0.01, grad_scale: float = 1.0,
+                    trust_ratio: Optional[torch.Tensor] = None, stream=None) -> None:
+    for t in (master, grad, m, v):
+        if t.dtype != torch.float32:
+            raise TypeError("master weights, gradient and moments must be fp32")
+    cfg = _LambConfig(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+    st = load_library().swarm_lamb_step(C.byref(cfg), master.numel(), _ptr(master), _ptr(param),
+                                        _dtype_code(param) if param is not None else SWARM_F32, _ptr(grad), _ptr(m),
+                                        _ptr(v), _ptr(trust_ratio), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_lamb_step")

@@ -1,0 +1,173 @@
+// LAMB step for one parameter tensor (appendix "Additional Details for Section 4.3").  Three streaming kernels:
+// moments + update direction + per-workgroup partial sums of |w|^2 and |u|^2; a single-workgroup, fixed-order
+// reduction to the trust ratio; the weight update (and the copy in the stage's dtype).
+#include <cmath>
+
+#include "kernels.h"
+#include "swarm_optim.h"
+
+namespace swarm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kPerThread = 16;                         // elements per thread in the first pass (4 x float4)
+constexpr int kPerBlock = kThreads * kPerThread;
+
+struct Hyper {
+  float beta1, beta2, one_m_beta1, one_m_beta2, inv_bc1, inv_bc2, eps, wd, gscale, lr;
+};
+
+__global__ __launch_bounds__(kThreads) void lamb_moments_kernel(const float* __restrict__ w, const float* __restrict__ g,
+                                                                float* __restrict__ m, float* __restrict__ v,
+                                                                float* __restrict__ u, float* __restrict__ partial,
+                                                                size_t n, Hyper h) {
+  __shared__ float s_w[kThreads], s_u[kThreads];
+  const size_t base = (size_t)blockIdx.x * kPerBlock;
+  float sw = 0.f, su = 0.f;
+#pragma unroll
+  for (int it = 0; it < kPerThread / 4; ++it) {
+    const size_t i = base + ((size_t)it * kThreads + threadIdx.x) * 4;
+    if (i + 4 <= n) {
+      const float4 w4 = *reinterpret_cast<const float4*>(w + i), g4 = *reinterpret_cast<const float4*>(g + i);
+      float4 m4 = *reinterpret_cast<const float4*>(m + i), v4 = *reinterpret_cast<const float4*>(v + i), u4;
+      const float wv[4] = {w4.x, w4.y, w4.z, w4.w}, gv[4] = {g4.x, g4.y, g4.z, g4.w};
+      float mv[4] = {m4.x, m4.y, m4.z, m4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w}, uv[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gs = gv[e] * h.gscale;
+        mv[e] = h.beta1 * mv[e] + h.one_m_beta1 * gs;
+        vv[e] = h.beta2 * vv[e] + h.one_m_beta2 * gs * gs;
+        uv[e] = (mv[e] * h.inv_bc1) / (sqrtf(vv[e] * h.inv_bc2) + h.eps) + h.wd * wv[e];
+        sw += wv[e] * wv[e];
+        su += uv[e] * uv[e];
+      }
+      m4 = make_float4(mv[0], mv[1], mv[2], mv[3]); v4 = make_float4(vv[0], vv[1], vv[2], vv[3]);
+      u4 = make_float4(uv[0], uv[1], uv[2], uv[3]);
+      *reinterpret_cast<float4*>(m + i) = m4; *reinterpret_cast<float4*>(v + i) = v4;
+      *reinterpret_cast<float4*>(u + i) = u4;
+    } else {
+      for (size_t j = i; j < n && j < i + 4; ++j) {          // ragged tail
+        const float gs = g[j] * h.gscale;
+        const float mj = h.beta1 * m[j] + h.one_m_beta1 * gs;
+        const float vj = h.beta2 * v[j] + h.one_m_beta2 * gs * gs;
+        const float uj = (mj * h.inv_bc1) / (sqrtf(vj * h.inv_bc2) + h.eps) + h.wd * w[j];
+        m[j] = mj; v[j] = vj; u[j] = uj;
+        sw += w[j] * w[j];
+        su += uj * uj;
+      }
+    }
+  }
+  s_w[threadIdx.x] = sw; s_u[threadIdx.x] = su;
+  __syncthreads();
+  for (int k = kThreads / 2; k >= 1; k >>= 1) {
+    if (threadIdx.x < k) { s_w[threadIdx.x] += s_w[threadIdx.x + k]; s_u[threadIdx.x] += s_u[threadIdx.x + k]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { partial[2 * (size_t)blockIdx.x] = s_w[0]; partial[2 * (size_t)blockIdx.x + 1] = s_u[0]; }
+}
+
+// ratio = |w| / |u| (1 if either is zero); doubles keep the long fixed-order sum accurate
+__global__ __launch_bounds__(kThreads) void lamb_ratio_kernel(const float* __restrict__ partial, size_t nblocks,
+                                                              float* __restrict__ ratio_out, float* __restrict__ user) {
+  __shared__ double s_w[kThreads], s_u[kThreads];
+  double sw = 0.0, su = 0.0;
+  for (size_t b = threadIdx.x; b < nblocks; b += kThreads) { sw += partial[2 * b]; su += partial[2 * b + 1]; }
+  s_w[threadIdx.x] = sw; s_u[threadIdx.x] = su;
+  __syncthreads();
+  for (int k = kThreads / 2; k >= 1; k >>= 1) {
+    if (threadIdx.x < k) { s_w[threadIdx.x] += s_w[threadIdx.x + k]; s_u[threadIdx.x] += s_u[threadIdx.x + k]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double nw = sqrt(s_w[0]), nu = sqrt(s_u[0]);
+    const float r = (nw > 0.0 && nu > 0.0) ? (float)(nw / nu) : 1.0f;
+    *ratio_out = r;
+    if (user) *user = r;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void lamb_apply_kernel(float* __restrict__ w, const float* __restrict__ u,
+                                                              T* __restrict__ param, const float* __restrict__ ratio,
+                                                              size_t n, float lr) {
+  const float step = lr * *ratio;
+  const size_t n4 = n / 4;
+  constexpr int U = kPerThread / 4;
+  const size_t i0 = (size_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+  float4 x[U], d[U];
+#pragma unroll
+  for (int it = 0; it < U; ++it) {
+    const size_t i = i0 + (size_t)it * kThreads;
+    if (i < n4) { x[it] = reinterpret_cast<const float4*>(w)[i]; d[it] = reinterpret_cast<const float4*>(u)[i]; }
+  }
+#pragma unroll
+  for (int it = 0; it < U; ++it) {
+    const size_t i = i0 + (size_t)it * kThreads;
+    if (i >= n4) continue;
+    float4 y = x[it];
+    y.x -= step * d[it].x; y.y -= step * d[it].y; y.z -= step * d[it].z; y.w -= step * d[it].w;
+    reinterpret_cast<float4*>(w)[i] = y;
+    if (param) {
+      if constexpr (sizeof(T) == 4) {
+        reinterpret_cast<float4*>(param)[i] = y;
+      } else {
+        T r[4];
+        Elem<T>::store(r, y.x); Elem<T>::store(r + 1, y.y); Elem<T>::store(r + 2, y.z); Elem<T>::store(r + 3, y.w);
+        reinterpret_cast<uint2*>(param)[i] = *reinterpret_cast<const uint2*>(r);
+      }
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < n - n4 * 4) {           // ragged tail
+    const size_t i = n4 * 4 + threadIdx.x;
+    const float x = w[i] - step * u[i];
+    w[i] = x;
+    if (param) Elem<T>::store(param + i, x);
+  }
+}
+
+size_t n_blocks(size_t n) { return (n + kPerBlock - 1) / kPerBlock; }
+
+}  // namespace
+}  // namespace swarm
+
+using namespace swarm;
+
+extern "C" size_t swarm_lamb_workspace_bytes(size_t n_elems) {
+  if (n_elems < 1) return 0;
+  const size_t u = (n_elems * 4 + 255) & ~(size_t)255;
+  const size_t p = (n_blocks(n_elems) * 8 + 255) & ~(size_t)255;
+  return u + p + 256;
+}
+
+extern "C" swarm_status swarm_lamb_step(const swarm_lamb_config* cfg, size_t n, float* master, void* param,
+                                        int32_t dtype, const float* grad, float* m, float* v, float* trust_ratio,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!cfg || !master || !grad || !m || !v || !workspace) return SWARM_ERR_NULL;
+  if (param && dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (n < 1 || cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) ||
+      !(cfg->eps > 0.f) || !(cfg->lr >= 0.f) || !(cfg->weight_decay >= 0.f))
+    return SWARM_ERR_SHAPE;
+  auto al16 = [](const void* q) { return ((uintptr_t)q & 15) == 0; };
+  if (!al16(master) || !al16(grad) || !al16(m) || !al16(v) || !al16(param) || ((uintptr_t)workspace & 255)) return SWARM_ERR_SHAPE;
+  if (swarm_lamb_workspace_bytes(n) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  float* u = (float*)workspace;
+  float* partial = (float*)((char*)workspace + ((n * 4 + 255) & ~(size_t)255));
+  const size_t nb = n_blocks(n);
+  float* ratio = partial + 2 * nb + (64 - (2 * nb) % 64) % 64;   // behind the partial sums, inside the slack
+  Hyper h;
+  h.beta1 = cfg->beta1; h.beta2 = cfg->beta2; h.one_m_beta1 = 1.0f - cfg->beta1; h.one_m_beta2 = 1.0f - cfg->beta2;
+  h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, (double)cfg->step)));
+  h.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta2, (double)cfg->step)));
+  h.eps = cfg->eps; h.wd = cfg->weight_decay; h.gscale = cfg->grad_scale; h.lr = cfg->lr;
+  hipLaunchKernelGGL(lamb_moments_kernel, dim3((unsigned)nb), dim3(kThreads), 0, st, master, grad, m, v, u, partial, n, h);
+  hipLaunchKernelGGL(lamb_ratio_kernel, dim3(1), dim3(kThreads), 0, st, partial, nb, ratio, trust_ratio);
+  const unsigned grid = (unsigned)nb;   // one workgroup per kPerBlock elements, as in the first pass
+  if (param && dtype == SWARM_BF16)
+    hipLaunchKernelGGL(lamb_apply_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, master, u, (bf16_raw*)param,
+                       ratio, n, cfg->lr);
+  else
+    hipLaunchKernelGGL(lamb_apply_kernel<float>, dim3(grid), dim3(kThreads), 0, st, master, u, (float*)param, ratio, n,
+                       cfg->lr);
+  return launch_status();
+}

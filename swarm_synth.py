@@ -244,3 +244,33 @@ def make_head_inputs(wl: HeadWorkload):
     return (ids[0].to(torch.int32).numpy(), ids[1].to(torch.int32).numpy(),
             normal(wl.seed, "x", (wl.tokens, wl.d_model), 0.0, 1.0, bf),
             normal(wl.seed, "dx_emb", (wl.tokens, wl.d_model), 0.0, 1e-2, bf))
+
+
+# Optimiser step (appendix "Additional Details for Section 4.3"): LAMB over the parameter tensors of one stage.
+@dataclasses.dataclass(frozen=True)
+class LambWorkload:
+    name: str
+    dtype: str            # type of the stage's copy of the weights (master weights and moments are fp32)
+    shapes: tuple         # one entry per parameter tensor
+    seed: int = BASE_SEED + 300
+
+
+def _rope_geglu_block_shapes(d: int, f: int):
+    return ((d,), (d,), (3 * d, d), (3 * d,), (d, d), (d,), (d,), (d,), (2 * f, d), (2 * f,), (d, f), (d,))
+
+
+LAMB_WORKLOADS = {
+    # the tensors of the Section 4.3 stage (one shared rotary + GeGLU block, d_model 4096, d_ffn 16384)
+    "lamb_stage_rope_geglu_d4096": LambWorkload("lamb_stage_rope_geglu_d4096", "bf16",
+                                                _rope_geglu_block_shapes(4096, 16384), seed=BASE_SEED + 301),
+}
+
+
+def make_lamb_tensor(wl: LambWorkload, index: int, n: int = None):
+    """(w, grad) fp32 of tensor `index` (flattened, optionally only the first n elements' worth): weights
+    N(0, 0.02) (vectors: around 1), gradients N(0, 1e-3) as after averaging over a large batch."""
+    shape = wl.shapes[index]
+    n = int(np.prod(shape)) if n is None else n
+    w = normal(wl.seed, "lamb.w%d" % index, (n,), 1.0 if len(shape) == 1 else 0.0, 0.02, False)
+    g = normal(wl.seed, "lamb.g%d" % index, (n,), 0.0, 1e-3, False)
+    return w, g

@@ -126,3 +126,14 @@ def test_head_validation_without_gpu(lib):
     dummy = C.c_void_p(256)
     assert lib.swarm_embedding_backward(dummy, dummy, 1, 70000, 10, 64, dummy, None) == -2   # T > 65536
     assert lib.swarm_embedding_forward(dummy, dummy, 1, 4, 10, 60, dummy, None) == -2        # d % 8
+
+
+def test_lamb_validation_without_gpu(lib):
+    assert sw.swarm_lamb_workspace_bytes(0) == 0
+    assert sw.swarm_lamb_workspace_bytes(1000) >= 4000
+    cfg = binding._LambConfig(1e-3, 0.9, 0.95, 1e-6, 0.01, 1.0, 1)
+    assert lib.swarm_lamb_step(C.byref(cfg), 16, None, None, 0, None, None, None, None, None, 0, None) == -1
+    dummy = C.c_void_p(256)
+    bad = binding._LambConfig(1e-3, 0.9, 0.95, 1e-6, 0.01, 1.0, 0)                      # step 0
+    assert lib.swarm_lamb_step(C.byref(bad), 16, dummy, None, 0, dummy, dummy, dummy, None, dummy, 1 << 20, None) == -2
+    assert lib.swarm_lamb_step(C.byref(cfg), 16, dummy, None, 0, dummy, dummy, dummy, None, dummy, 8, None) == -4
