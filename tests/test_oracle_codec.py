@@ -177,3 +177,109 @@ def test_traffic_ratio_matches_paper():
     for src, approx in rows:
         ratio = float(src) / per_elem
         assert abs(ratio - float(approx)) / float(approx) < 0.07
+
+
+# ------------------------------------------------------------------ 16-bit scales
+def _round_to_bits(fr: Fraction, p: int, emin: int) -> Fraction:
+    """Nearest-even rounding of an exact rational to a binary format with p significand bits (hidden bit
+    included) and smallest normal exponent emin; exact integer arithmetic, subnormals included."""
+    if fr == 0:
+        return Fraction(0)
+    sign = -1 if fr < 0 else 1
+    fr = abs(fr)
+    e = fr.numerator.bit_length() - fr.denominator.bit_length()
+    if Fraction(2) ** e > fr:
+        e -= 1
+    if Fraction(2) ** (e + 1) <= fr:
+        e += 1
+    ulp = Fraction(2) ** (max(e, emin) - (p - 1))
+    q = fr / ulp
+    n = q.numerator // q.denominator
+    rem = q - n
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (n & 1)):
+        n += 1
+    return sign * n * ulp
+
+
+def _exact_encode_block_s16(xs):
+    fx = [Fraction(float(v)) for v in xs]
+    A = max(abs(v) for v in fx)
+    s32 = _round_to_bits(A / 127, 24, -126)                  # the fp32 division
+    fs = _round_to_bits(s32, 8, -126)                        # then once more, to bf16
+    if fs == 0:
+        return [0] * len(xs), fs
+    out = []
+    for v in fx:
+        qf = _round_to_bits(v / fs, 24, -126)
+        n = qf.numerator // qf.denominator
+        rem = qf - n
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (n & 1)):
+            n += 1
+        out.append(int(max(-127, min(127, n))))
+    return out, fs
+
+
+def test_round_to_bits_helper_against_numpy_and_torch():
+    import torch
+    rng = np.random.default_rng(1)
+    v = np.concatenate([rng.standard_normal(300) * 10.0 ** rng.integers(-42, 30, 300), [2.0 ** -133, 2.0 ** -134, 3 * 2.0 ** -135]])
+    v32 = v.astype(np.float32)
+    for x64, x32 in zip(v, v32):
+        assert float(_round_to_bits(Fraction(float(x64)), 24, -126)) == float(x32)
+    tb = torch.from_numpy(v32).to(torch.bfloat16).float().numpy()
+    for x32, xb in zip(v32, tb):
+        assert float(_round_to_bits(Fraction(float(x32)), 8, -126)) == float(xb)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("std", [1.0, 1e-2, 3e-5, 1e-38])
+def test_encode_s16_matches_exact_rational(bf16, std):
+    x = synth.codec_tensor(17, 64 * 24 + 17, std=1.0, bf16=bf16) * np.float32(std)
+    codes, sbits = codec.encode(x, 64, scale_bits=16)
+    assert sbits.dtype == np.uint16 and sbits.shape == ((x.size + 63) // 64,)
+    sval = codec.bf16_bits_to_f32(sbits)
+    for b in range(sbits.size):
+        ec, es = _exact_encode_block_s16(x[b * 64:(b + 1) * 64])
+        assert float(es) == float(sval[b])
+        assert ec == codes[b * 64:(b + 1) * 64].tolist()
+
+
+def test_s16_half_step_bound_extremes_and_fp32_path_untouched():
+    for std, bf in [(1.0, False), (1.0, True), (1e-2, True), (40.0, False)]:
+        x = synth.codec_tensor(12, 64 * 512, std=std, bf16=bf)
+        codes, sbits = codec.encode(x, scale_bits=16)
+        c32, s32 = codec.encode(x)
+        sval = codec.bf16_bits_to_f32(sbits)
+        assert np.all(np.abs(sval.astype(np.float64) - s32) <= s32.astype(np.float64) * 2.0 ** -8)   # one bf16 rounding
+        assert s32.dtype == np.float32 and np.any(sval != s32)
+        y = codec.decode(codes, sbits)
+        s = np.repeat(sval.astype(np.float64), 64)
+        err = np.abs(x.astype(np.float64) - y.astype(np.float64))
+        assert np.all(err <= s * (0.5 + 127 * 2.0 ** -22))          # also for the largest element (127 * 2^-8 < 1/2)
+        xb, cb = x.reshape(-1, 64), codes.reshape(-1, 64)
+        am, rows = np.argmax(np.abs(xb), axis=1), np.arange(xb.shape[0])
+        assert np.all(np.abs(cb[rows, am].astype(np.int32)) == 127) and cb.min() >= -127
+        assert np.mean(codes != c32) < 0.2                          # same grid up to the scale's last bit
+
+
+def test_s16_scale_flushes_to_zero_and_ragged_and_empty():
+    x = np.zeros(64 * 2 + 3, dtype=np.float32)
+    x[:64] = np.float32(2.0 ** -130)            # A / 127 = 2^-137 rounds to bf16 zero (half of the smallest
+    x[64:128] = np.float32(1.5)                 # subnormal 2^-133 is 2^-134)
+    x[128:] = [0.25, -1.0, 0.5]
+    codes, sbits = codec.encode(x, scale_bits=16)
+    assert sbits[0] == 0 and not codes[:64].any()
+    assert codes[64] == 127 and codes[129] == -127
+    ec, es = _exact_encode_block_s16(x[128:])
+    assert ec == codes[128:].tolist()
+    assert np.all(codec.decode(codes, sbits)[:64] == 0)
+    c0, s0 = codec.encode(np.zeros(0, dtype=np.float32), scale_bits=16)
+    assert c0.size == 0 and s0.size == 0 and s0.dtype == np.uint16
+
+
+def test_s16_traffic_ratio_matches_paper():
+    rows = [l.split() for l in open(os.path.join(HERE, "golden", "codec_traffic.txt")) if not l.startswith("#")]
+    per_elem = 1 + 2 / 64
+    for src, approx in rows:
+        ratio = float(src) / per_elem
+        assert abs(ratio - float(approx)) / float(approx) < 0.035   # twice as close to the quoted factors as fp32 scales
