@@ -130,6 +130,18 @@ swarm_status swarm_codec_encode(const void *tensor, int32_t dtype, size_t n_elem
 swarm_status swarm_codec_decode(const int8_t *codes, const float *scales, size_t n_elems, int32_t block,
                                 void *tensor, int32_t dtype, void *hip_stream);
 
+/* The same codec with 16-bit block scales (1.03125 instead of 1.0625 bytes per element; the paragraph puts the
+ * saving against 16-bit tensors at about a factor 2): scale = bf16(max|x| / 127), nearest-even, stored as its bit pattern, and the
+ * codes divide by that ROUNDED scale: code = scale == 0 ? 0 : clamp(rint(x / scale), -127, 127).  The rounding
+ * moves the scale by at most 2^-8 relative, so the largest element still gets +-127 and every element's round-trip
+ * error stays within half a step; a block whose scale rounds to zero (max|x| < 2^-127) is encoded as zeros.
+ * scales [ceil(n/block)] uint16, 2-byte aligned; everything else as in swarm_codec_encode / swarm_codec_decode.
+ * The fused stage entry points below use fp32 scales only. */
+swarm_status swarm_codec_encode_s16(const void *tensor, int32_t dtype, size_t n_elems, int32_t block,
+                                    int8_t *codes, uint16_t *scales, void *hip_stream);
+swarm_status swarm_codec_decode_s16(const int8_t *codes, const uint16_t *scales, size_t n_elems, int32_t block,
+                                    void *tensor, int32_t dtype, void *hip_stream);
+
 /* The same two stage calls with the 8-bit codec of the "Quantized activations" paragraph fused into the
  * stage boundary: a peer receives int8-compressed activations / output gradients and sends int8-compressed
  * outputs / input gradients, so the boundary tensors need not be materialised twice.  Results are

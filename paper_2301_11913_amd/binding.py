@@ -18,7 +18,8 @@ EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm
                     "swarm_decompress_forward", "swarm_decompress_backward",
                     "swarm_embedding_forward", "swarm_embedding_backward", "swarm_head_workspace_bytes",
                     "swarm_head_loss", "swarm_head_loss_backward",
-                    "swarm_lamb_workspace_bytes", "swarm_lamb_step")
+                    "swarm_lamb_workspace_bytes", "swarm_lamb_step",
+                    "swarm_codec_encode_s16", "swarm_codec_decode_s16")
 SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -133,6 +134,10 @@ def load_library():
     lib.swarm_codec_decode.restype = C.c_int
     lib.swarm_codec_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_int32,
                                        C.c_void_p]
+    lib.swarm_codec_encode_s16.restype = C.c_int
+    lib.swarm_codec_encode_s16.argtypes = lib.swarm_codec_encode.argtypes
+    lib.swarm_codec_decode_s16.restype = C.c_int
+    lib.swarm_codec_decode_s16.argtypes = lib.swarm_codec_decode.argtypes
     lib.swarm_stage_coded_workspace_bytes.restype = C.c_size_t
     lib.swarm_stage_coded_workspace_bytes.argtypes = [C.POINTER(_Config), C.c_int]
     lib.swarm_stage_forward_coded.restype = C.c_int
@@ -261,6 +266,27 @@ def swarm_codec_decode(codes: torch.Tensor, scales: torch.Tensor, tensor: torch.
                                            _dtype_code(tensor), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_codec_decode")
+
+
+def swarm_codec_encode_s16(tensor: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, block: int = 64,
+                           stream=None) -> None:
+    """scales: int16 / uint16 tensor receiving bf16 bit patterns (or a bf16 tensor, which is the same memory)."""
+    if codes.dtype != torch.int8 or scales.element_size() != 2:
+        raise TypeError("codes must be int8 and scales a 16-bit tensor")
+    st = load_library().swarm_codec_encode_s16(_ptr(tensor), _dtype_code(tensor), tensor.numel(), block, _ptr(codes),
+                                               _ptr(scales), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_codec_encode_s16")
+
+
+def swarm_codec_decode_s16(codes: torch.Tensor, scales: torch.Tensor, tensor: torch.Tensor, block: int = 64,
+                           stream=None) -> None:
+    if codes.dtype != torch.int8 or scales.element_size() != 2:
+        raise TypeError("codes must be int8 and scales a 16-bit tensor")
+    st = load_library().swarm_codec_decode_s16(_ptr(codes), _ptr(scales), tensor.numel(), block, _ptr(tensor),
+                                               _dtype_code(tensor), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_codec_decode_s16")
 
 
 def swarm_stage_coded_workspace_bytes(cfg: StageConfig, for_backward: bool) -> int:

@@ -48,6 +48,19 @@ template <> struct Vec8<float> {
   }
 };
 
+// Block scale as stored: fp32, or its bf16 rounding as a 16-bit pattern (the codes then divide by the ROUNDED scale).
+template <typename S> struct ScaleIO;
+template <> struct ScaleIO<float> {
+  static __device__ __forceinline__ float round(float s) { return s; }
+  static __device__ __forceinline__ void store(float* p, float s) { *p = s; }
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+};
+template <> struct ScaleIO<uint16_t> {
+  static __device__ __forceinline__ float round(float s) { return __uint_as_float(float_to_bf16_bits(s) << 16); }
+  static __device__ __forceinline__ void store(uint16_t* p, float s) { *p = (uint16_t)(__float_as_uint(s) >> 16); }
+  static __device__ __forceinline__ float load(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+};
+
 __device__ __forceinline__ int quantise(float x, float scale) {
   float q = rintf(x / scale);
   q = fminf(fmaxf(q, -127.0f), 127.0f);
@@ -55,10 +68,10 @@ __device__ __forceinline__ int quantise(float x, float scale) {
 }
 
 // Full 8-element groups: n8 = n_elems / 8 groups, each handled by one lane.
-template <typename T>
+template <typename T, typename S = float>
 __global__ __launch_bounds__(kThreads) void codec_encode_kernel(const T* __restrict__ src, size_t n_elems,
                                                                 int8_t* __restrict__ codes,
-                                                                float* __restrict__ scales) {
+                                                                S* __restrict__ scales) {
   const size_t n_groups = (n_elems + kPerLane - 1) / kPerLane;
   const size_t stride = (size_t)gridDim.x * kThreads;
   // all lanes of an octet run the same number of iterations: n_groups is padded to a multiple of 8 below
@@ -78,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void codec_encode_kernel(const T* __restr
     a = fmaxf(a, __shfl_xor(a, 1, 64));
     a = fmaxf(a, __shfl_xor(a, 2, 64));
     a = fmaxf(a, __shfl_xor(a, 4, 64));
-    const float scale = a / 127.0f;
+    const float scale = ScaleIO<S>::round(a / 127.0f);
     int c[8];
     if (scale == 0.0f) {
 #pragma unroll
@@ -99,19 +112,19 @@ __global__ __launch_bounds__(kThreads) void codec_encode_kernel(const T* __restr
       for (int i = 0; i < 8; ++i)
         if (base + i < n_elems) codes[base + i] = (int8_t)c[i];
     }
-    if ((g & 7) == 0 && base < n_elems) scales[g >> 3] = scale;
+    if ((g & 7) == 0 && base < n_elems) ScaleIO<S>::store(scales + (g >> 3), scale);
   }
 }
 
-template <typename T>
+template <typename T, typename S = float>
 __global__ __launch_bounds__(kThreads) void codec_decode_kernel(const int8_t* __restrict__ codes,
-                                                                const float* __restrict__ scales, size_t n_elems,
+                                                                const S* __restrict__ scales, size_t n_elems,
                                                                 T* __restrict__ dst) {
   const size_t n_groups = (n_elems + kPerLane - 1) / kPerLane;
   const size_t stride = (size_t)gridDim.x * kThreads;
   for (size_t g = (size_t)blockIdx.x * kThreads + threadIdx.x; g < n_groups; g += stride) {
     const size_t base = g * kPerLane;
-    const float scale = scales[g >> 3];
+    const float scale = ScaleIO<S>::load(scales + (g >> 3));
     float y[8];
     if (base + kPerLane <= n_elems) {
       uint2 v = *reinterpret_cast<const uint2*>(codes + base);
@@ -185,4 +198,40 @@ extern "C" swarm_status swarm_codec_decode(const int8_t* codes, const float* sca
   if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
   if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 3)) return SWARM_ERR_SHAPE;
   return codec_decode_launch(codes, scales, n_elems, tensor, dtype == SWARM_BF16, (hipStream_t)hip_stream);
+}
+
+extern "C" swarm_status swarm_codec_encode_s16(const void* tensor, int32_t dtype, size_t n_elems, int32_t block,
+                                               int8_t* codes, uint16_t* scales, void* hip_stream) {
+  if (block != kBlock) return SWARM_ERR_SHAPE;
+  if (dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (n_elems == 0) return SWARM_OK;
+  if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
+  if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 1)) return SWARM_ERR_SHAPE;
+  const int grid = codec_grid(n_elems);
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dtype == SWARM_BF16)
+    hipLaunchKernelGGL((codec_encode_kernel<bf16_raw, uint16_t>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_raw*)tensor, n_elems, codes, scales);
+  else
+    hipLaunchKernelGGL((codec_encode_kernel<float, uint16_t>), dim3(grid), dim3(kThreads), 0, st, (const float*)tensor,
+                       n_elems, codes, scales);
+  return launch_status();
+}
+
+extern "C" swarm_status swarm_codec_decode_s16(const int8_t* codes, const uint16_t* scales, size_t n_elems,
+                                               int32_t block, void* tensor, int32_t dtype, void* hip_stream) {
+  if (block != kBlock) return SWARM_ERR_SHAPE;
+  if (dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (n_elems == 0) return SWARM_OK;
+  if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
+  if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 1)) return SWARM_ERR_SHAPE;
+  const int grid = codec_grid(n_elems);
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dtype == SWARM_BF16)
+    hipLaunchKernelGGL((codec_decode_kernel<bf16_raw, uint16_t>), dim3(grid), dim3(kThreads), 0, st, codes, scales,
+                       n_elems, (bf16_raw*)tensor);
+  else
+    hipLaunchKernelGGL((codec_decode_kernel<float, uint16_t>), dim3(grid), dim3(kThreads), 0, st, codes, scales,
+                       n_elems, (float*)tensor);
+  return launch_status();
 }

@@ -16,7 +16,7 @@ def _header_symbols():
     text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
                    if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(swarm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(swarm_[a-z0-9_]+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -137,3 +137,16 @@ def test_lamb_validation_without_gpu(lib):
     bad = binding._LambConfig(1e-3, 0.9, 0.95, 1e-6, 0.01, 1.0, 0)                      # step 0
     assert lib.swarm_lamb_step(C.byref(bad), 16, dummy, None, 0, dummy, dummy, dummy, None, dummy, 1 << 20, None) == -2
     assert lib.swarm_lamb_step(C.byref(cfg), 16, dummy, None, 0, dummy, dummy, dummy, None, dummy, 8, None) == -4
+
+
+def test_codec_s16_validation_without_gpu(lib):
+    dummy = C.c_void_p(256)
+    for fn in (lib.swarm_codec_encode_s16, lib.swarm_codec_decode_s16):
+        fn.restype = C.c_int
+    enc = lambda *a: lib.swarm_codec_encode_s16(*a)
+    assert enc(dummy, 1, C.c_size_t(0), 64, dummy, dummy, None) == 0                 # empty: no-op
+    assert enc(dummy, 1, C.c_size_t(64), 32, dummy, dummy, None) == -2               # block must be 64
+    assert enc(dummy, 7, C.c_size_t(64), 64, dummy, dummy, None) == -3               # dtype
+    assert enc(None, 1, C.c_size_t(64), 64, dummy, dummy, None) == -1
+    assert enc(dummy, 1, C.c_size_t(64), 64, dummy, C.c_void_p(257), None) == -2     # scales 2-byte aligned
+    assert lib.swarm_codec_decode_s16(dummy, None, C.c_size_t(64), 64, dummy, 1, None) == -1

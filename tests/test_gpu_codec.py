@@ -100,3 +100,52 @@ def test_codec_full_boundary_tensor():
     assert np.array_equal(rs.view(np.uint32), gs.view(np.uint32))
     assert np.array_equal(rc, gc)
     assert np.array_equal(ocodec.decode(rc, rs, out="bf16"), _decode_gpu(rc, rs, n, True))
+
+
+# ------------------------------------------------------------------ 16-bit scales
+def _encode_gpu_s16(x, bf16):
+    import paper_2301_11913_amd as sw
+    t = _dev(x, bf16)
+    n = t.numel()
+    codes = torch.full((n,), 77, dtype=torch.int8, device="cuda")
+    scales = torch.full(((n + 63) // 64,), -1, dtype=torch.int16, device="cuda")
+    sw.swarm_codec_encode_s16(t, codes, scales)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.cpu().numpy().view(np.uint16)
+
+
+def _decode_gpu_s16(codes, sbits, n, bf16):
+    import paper_2301_11913_amd as sw
+    out = torch.full((n,), 3.0, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+    sw.swarm_codec_decode_s16(torch.from_numpy(codes).cuda(), torch.from_numpy(sbits.view(np.int16)).cuda(), out)
+    torch.cuda.synchronize()
+    return out.view(torch.int16).cpu().numpy().view(np.uint16) if bf16 else out.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("std", [1.0, 1e-2, 1e-38])
+def test_codec_s16_bit_exact(bf16, n, std):
+    x = synth.codec_tensor(131 + n, n, std=std, bf16=bf16)
+    if n > 200:
+        x[64:128] = 0.0
+        x[128:192] = np.float32(2.0 ** -130)          # scale rounds to zero in bf16
+    rc, rs = ocodec.encode(x, scale_bits=16)
+    gc, gs = _encode_gpu_s16(x, bf16)
+    assert np.array_equal(rs, gs)
+    assert np.array_equal(rc, gc)
+    ry = ocodec.decode(rc, rs, out="bf16" if bf16 else "f32")
+    gy = _decode_gpu_s16(rc, rs, n, bf16)
+    assert np.array_equal(ry if bf16 else ry.view(np.uint32), gy)
+
+
+def test_codec_s16_all_bf16_patterns():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = ocodec.bf16_bits_to_f32(bits)
+    vals = vals[np.isfinite(vals)]
+    for x in (np.sort(vals), np.random.default_rng(6).permutation(vals)):
+        x = x[: (x.size // 64) * 64]
+        rc, rs = ocodec.encode(x, scale_bits=16)
+        gc, gs = _encode_gpu_s16(x, True)
+        assert np.array_equal(rs, gs) and np.array_equal(rc, gc)
+        assert np.array_equal(ocodec.decode(rc, rs, out="bf16"), _decode_gpu_s16(rc, rs, x.size, True))

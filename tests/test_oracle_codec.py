@@ -234,7 +234,7 @@ def test_round_to_bits_helper_against_numpy_and_torch():
 @pytest.mark.parametrize("bf16", [False, True])
 @pytest.mark.parametrize("std", [1.0, 1e-2, 3e-5, 1e-38])
 def test_encode_s16_matches_exact_rational(bf16, std):
-    x = synth.codec_tensor(17, 64 * 24 + 17, std=1.0, bf16=bf16) * np.float32(std)
+    x = synth.codec_tensor(17, 64 * 24 + 17, std=std, bf16=bf16)
     codes, sbits = codec.encode(x, 64, scale_bits=16)
     assert sbits.dtype == np.uint16 and sbits.shape == ((x.size + 63) // 64,)
     sval = codec.bf16_bits_to_f32(sbits)
