@@ -24,9 +24,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0             # MI355X HBM3E
 
 
-def measured_traffic(workload):
-    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary (None if there is none)."""
-    path = os.path.join(ROOT, "profiles", "gemm_bf16_%s_hbm_traffic.json" % workload)
+def measured_traffic(workload, kernel="gemm_bf16"):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (None if there is none)."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.json" % (kernel, workload))
     try:
         with open(path) as f:
             return json.load(f)["hbm_bytes_per_launch"]
@@ -287,6 +287,13 @@ def bench_lamb(args):
         e1.record()
     torch.cuda.synchronize()
     ms_big = sum(e0.elapsed_time(e1) for e0, e1 in ev) / len(ev)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # per element: first pass reads w, g, m, v and writes m, v, u (28 B); update reads w, u, writes w and the copy
     bytes_per_elem = 28 + 12 + (2 if wl.dtype == "bf16" else 4)
     achieved = bytes_per_elem * sizes[big] / (ms_big * 1e-3) / 1e9
@@ -298,7 +305,10 @@ def bench_lamb(args):
            "config": {"workload": wl.name, "tensors": len(sizes), "parameters": n_total, "param_copy": wl.dtype},
            "roofline": {"bound": "hbm", "kernel": "lamb_moments_kernel + lamb_ratio_kernel + lamb_apply_kernel",
                         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(wl.name),
+                        "frac": round(achieved / HBM_PEAK_GBS, 4),
+                        # measured bytes of one update of the largest tensor: first pass + update kernel
+                        "traffic": (lambda a, b: None if a is None or b is None else a + b)(
+                            measured_traffic(wl.name, "lamb_moments"), measured_traffic(wl.name, "lamb_apply")),
                         "elements": sizes[big], "bytes_per_element": bytes_per_elem, "avg_update_us": round(ms_big * 1e3, 1)}}
     if not args.no_cpu_baseline:
         from oracle.lamb import lamb_step

@@ -2,10 +2,12 @@
 
     python -m paper_2301_11913_amd.profile_summary stats  <dir>/<prefix>_kernel_stats.csv
     python -m paper_2301_11913_amd.profile_summary pmc    <fetch>_counter_collection.csv <write>_counter_collection.csv
+                                                          [kernel name prefix = gemm_bf16 [largest]]
 
 `pmc` expects two runs of `bench.py --copy-calibration` under `rocprofv3 --pmc FETCH_SIZE` and
 `--pmc WRITE_SIZE`.  The counters are scaled by what they read for the plain 1 GiB device copies of
-that run (each reads 2^30 and writes 2^30 bytes), then averaged over the launches of the bf16 GEMM kernels.
+that run (each reads 2^30 and writes 2^30 bytes), then averaged over the launches of the kernels whose name starts
+with the prefix (with `largest`: only over the launches with the largest grid, i.e. the largest tensor).
 """
 from __future__ import annotations
 
@@ -40,25 +42,31 @@ def stats(path: str) -> None:
 
 
 def _per_kernel(path: str, counter: str):
+    """kernel name -> [(counter value, grid size)] over its launches"""
     acc = collections.defaultdict(list)
     for r in csv.DictReader(open(path)):
         if r["Counter_Name"] == counter:
-            acc[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
+            acc[_short(r["Kernel_Name"])].append((float(r["Counter_Value"]), int(r.get("Grid_Size", 0) or 0)))
     return acc
 
 
-def pmc(fetch_csv: str, write_csv: str) -> None:
-    out = {}
+def pmc(fetch_csv: str, write_csv: str, prefix: str = "gemm_bf16", which: str = "all") -> None:
+    out = {"kernel_prefix": prefix, "launches_counted": which}
+    key = "gemm" if prefix == "gemm_bf16" else "kernel"
     for counter, path in (("FETCH_SIZE", fetch_csv), ("WRITE_SIZE", write_csv)):
         acc = _per_kernel(path, counter)
-        copies = [v for k, vals in acc.items() if "copy" in k.lower() or "Copy" in k for v in vals]
+        copies = [v for k, vals in acc.items() if "copy" in k.lower() or "Copy" in k for v, _ in vals]
         big = [v for v in copies if v > 0.75 * max(copies)]         # the 1 GiB calibration copies (a dtype-converting
                                                                    # copy of a 0.5 GiB tensor reads half as much)
         per_unit = GIB / (sum(big) / len(big))                      # bytes per counter unit
-        gemm = [v for k, vals in acc.items() if k.startswith("gemm_bf16") for v in vals]
+        sel = [(v, g) for k, vals in acc.items() if k.startswith(prefix) for v, g in vals]
+        if which == "largest":
+            gmax = max(g for _, g in sel)
+            sel = [(v, g) for v, g in sel if g == gmax]
+        vals = [v for v, _ in sel]
         out[counter] = {"calibration_copies": len(big), "bytes_per_counter_unit": per_unit,
-                        "gemm_launches": len(gemm), "gemm_bytes_per_launch": per_unit * sum(gemm) / len(gemm)}
-    out["hbm_bytes_per_launch"] = out["FETCH_SIZE"]["gemm_bytes_per_launch"] + out["WRITE_SIZE"]["gemm_bytes_per_launch"]
+                        key + "_launches": len(vals), key + "_bytes_per_launch": per_unit * sum(vals) / len(vals)}
+    out["hbm_bytes_per_launch"] = out["FETCH_SIZE"][key + "_bytes_per_launch"] + out["WRITE_SIZE"][key + "_bytes_per_launch"]
     print(json.dumps(out, indent=1))
 
 
