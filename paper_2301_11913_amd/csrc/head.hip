@@ -61,8 +61,8 @@ __global__ __launch_bounds__(kThreads) void embedding_fwd_kernel(const int32_t* 
 }
 
 // grad_table[id, :] += sum over positions t' with token[t'] == id of dx[t', :], in increasing t'.
-// Workgroup t does the whole sum if t is the first position of its id, otherwise nothing: no two workgroups touch
-// the same row, no atomics.  Positions are scanned 256 at a time; the matches of a round are put into LDS in
+// The workgroups (t, y) do the whole sum (each for its own 2048 columns) if t is the first position of its id,
+// otherwise nothing: no two workgroups touch the same elements, no atomics.  Positions are scanned 256 at a time; the matches of a round are put into LDS in
 // position order (wave ballots + popcounts), then every thread adds those rows to its own columns.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void embedding_bwd_kernel(const int32_t* __restrict__ tokens,
@@ -82,13 +82,13 @@ __global__ __launch_bounds__(kThreads) void embedding_bwd_kernel(const int32_t* 
   __syncthreads();
   if (s_flag) return;
 
-  constexpr int MAXC = 4;        // column chunks of 8 per thread: d <= 8192
-  const int nch = d >> 3;
-  float acc[MAXC][8];
+  // blockIdx.y picks this workgroup's 256 column chunks of 8 (a frequent id has hundreds of rows to add: the
+  // columns are spread over several workgroups and the row loads go out eight at a time)
+  const int c = blockIdx.y * kThreads + threadIdx.x;
+  const bool live = c < (d >> 3);
+  float acc[8];
 #pragma unroll
-  for (int q = 0; q < MAXC; ++q)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int base = t0; base < n_tokens; base += kThreads) {
     const int t = base + threadIdx.x;
@@ -104,29 +104,29 @@ __global__ __launch_bounds__(kThreads) void embedding_bwd_kernel(const int32_t* 
     }
     if (match) s_list[before + __popcll(ballot & ((1ull << lane) - 1ull))] = t;
     __syncthreads();
-    for (int j = 0; j < total; ++j) {
-      const T* row = dx + (size_t)s_list[j] * d;
+    if (live) {
+      constexpr int U = 8;
+      for (int j0 = 0; j0 < total; j0 += U) {
+        float v[U][8];
 #pragma unroll
-      for (int q = 0; q < MAXC; ++q) {
-        const int c = threadIdx.x + q * kThreads;
-        if (c < nch) {
-          float v[8];
-          ld8<T>(row + c * 8, v);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[q][e] += v[e];
+        for (int u = 0; u < U; ++u) {
+          const int j = min(j0 + u, total - 1);            // past the end: a re-read that is not added
+          ld8<T>(dx + (size_t)s_list[j] * d + c * 8, v[u]);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (j0 + u < total) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
+          }
       }
     }
     __syncthreads();             // s_list and s_wave_cnt are rewritten by the next round
   }
-  float* out = grad + (size_t)id * d;
+  if (live) {
+    float* out = grad + (size_t)id * d + c * 8;
 #pragma unroll
-  for (int q = 0; q < MAXC; ++q) {
-    const int c = threadIdx.x + q * kThreads;
-    if (c < nch) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) out[c * 8 + e] += acc[q][e];
-    }
+    for (int e = 0; e < 8; ++e) out[e] += acc[e];
   }
 }
 
@@ -322,11 +322,12 @@ extern "C" swarm_status swarm_embedding_backward(const int32_t* tokens, const vo
   if (n_tokens < 1 || n_tokens > 65536 || vocab < 1 || d_model < 8 || d_model % 8 || d_model > 8192 || !al16(dx))
     return SWARM_ERR_SHAPE;
   hipStream_t st = (hipStream_t)hip_stream;
+  const dim3 grid(n_tokens, (d_model / 8 + kThreads - 1) / kThreads);
   if (dtype == SWARM_BF16)
-    hipLaunchKernelGGL(embedding_bwd_kernel<bf16_raw>, dim3(n_tokens), dim3(kThreads), 0, st, tokens,
+    hipLaunchKernelGGL(embedding_bwd_kernel<bf16_raw>, grid, dim3(kThreads), 0, st, tokens,
                        (const bf16_raw*)dx, grad_table, n_tokens, vocab, d_model);
   else
-    hipLaunchKernelGGL(embedding_bwd_kernel<float>, dim3(n_tokens), dim3(kThreads), 0, st, tokens, (const float*)dx,
+    hipLaunchKernelGGL(embedding_bwd_kernel<float>, grid, dim3(kThreads), 0, st, tokens, (const float*)dx,
                        grad_table, n_tokens, vocab, d_model);
   return launch_status();
 }
