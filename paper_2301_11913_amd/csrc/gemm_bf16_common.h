@@ -23,12 +23,15 @@ struct KArgs {
   int split;       // EPI_DGEGLU, EPI_BIAS_GEGLU
   int tiles_m, tiles_n;
   int group_m;   // tile rows walked together (L2 reuse of the B panel)
+  int ksplit;    // > 1: the grid holds ksplit workgroups per tile, each takes K / ksplit and stores its fp32 partial
+  float* part;   //      tile sums to part + index * M * N (a second kernel adds them and applies the epilogue)
 };
+
+constexpr int EPI_PART_F32 = 100;   // kernel-internal: C (fp32, ldc = N) = acc, no read
 
 // Launch order maps consecutive workgroups to the 8 XCDs round-robin; give every XCD a contiguous band
 // of tiles (its own L2 then sees the reuse) and walk tiles in groups of 8 rows to keep a B panel resident.
-__device__ __forceinline__ void tile_of_block(const KArgs& p, int& tile_m, int& tile_n) {
-  int pid = blockIdx.x;
+__device__ __forceinline__ void tile_of_block(const KArgs& p, int& tile_m, int& tile_n, int pid = blockIdx.x) {
   const int ntiles = p.tiles_m * p.tiles_n;
   if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
   const int GM = p.group_m;
@@ -75,8 +78,8 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
   const int epi = p.epilogue;
   constexpr int COLS = 32 * FN;
   const int lane = l32 + 32 * lg;
-  if (epi == EPI_ACCUM_F32) {
-    // C (fp32) += acc, 16 bytes per lane: 16 lanes cover one 64-column row of the sub-tile
+  if (epi == EPI_ACCUM_F32 || epi == EPI_PART_F32) {
+    // C (fp32) += acc (or = acc), 16 bytes per lane: 16 lanes cover one 64-column row of the sub-tile
     constexpr int LPR4 = COLS / 4, RPP4 = 64 / LPR4;
     float* c = reinterpret_cast<float*>(p.C);
     const int c4 = lane % LPR4, rsub4 = lane / LPR4;
@@ -96,8 +99,11 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
         const float4 v = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 4 * c4);
         if (!colf_ok || (GUARD && row >= p.M)) continue;
         float4* dst = reinterpret_cast<float4*>(c + (size_t)row * p.ldc + colf);
-        float4 o = *dst;
-        o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        float4 o = v;
+        if (epi == EPI_ACCUM_F32) {
+          o = *dst;
+          o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        }
         *dst = o;
       }
     }

@@ -125,7 +125,20 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
 
   int tile_m, tile_n;
-  tile_of_block(p, tile_m, tile_n);
+  if (p.ksplit > 1) {
+    // workgroups [i * ntiles, (i+1) * ntiles) take the i-th part of K of every tile
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int part = blockIdx.x / ntiles;
+    tile_of_block(p, tile_m, tile_n, blockIdx.x - part * ntiles);
+    p.K /= p.ksplit;
+    p.A += A_T ? (size_t)part * p.K * p.lda : (size_t)part * p.K;
+    p.B += B_T ? (size_t)part * p.K * p.ldb : (size_t)part * p.K;
+    p.C = p.part + (size_t)part * p.M * p.N;
+    p.ldc = p.N;
+    p.epilogue = EPI_PART_F32;
+  } else {
+    tile_of_block(p, tile_m, tile_n);
+  }
   const int m0 = tile_m * BM;
   // GeGLU forward: a tile of BN gathered rows covers BN/2 features; n0 then counts features
   const int glu = (!B_T && p.epilogue == EPI_BIAS_GEGLU) ? p.split : 0;
@@ -270,7 +283,8 @@ swarm_status launch_dma(const KArgs& k, hipStream_t st) {
       return SWARM_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n), dim3(WM * WN * 64), lds_bytes, st, k);
+  hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n * (k.ksplit > 1 ? k.ksplit : 1)), dim3(WM * WN * 64), lds_bytes,
+                     st, k);
   return launch_status();
 }
 
@@ -282,7 +296,79 @@ swarm_status launch_dma_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t s
   return SWARM_ERR_SHAPE;
 }
 
+// ---- split-K: second kernel.  C = epilogue(part_0 + part_1 + ...), summed in index order; a lane owns 8 columns.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(KArgs p) {
+  const size_t chunks_per_row = (size_t)p.N / 8;
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (size_t)p.M * chunks_per_row) return;         // whole lane octets leave together (N % 64 == 0)
+  const size_t row = idx / chunks_per_row;
+  const int col = (int)(idx % chunks_per_row) * 8;
+  const size_t mn = (size_t)p.M * p.N;
+  float x[8];
+  {
+    const float4* q = reinterpret_cast<const float4*>(p.part + row * p.N + col);
+    const float4 a = q[0], b = q[1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+  for (int i = 1; i < p.ksplit; ++i) {
+    const float4* q = reinterpret_cast<const float4*>(p.part + i * mn + row * p.N + col);
+    const float4 a = q[0], b = q[1];
+    x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w; x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
+  }
+  if constexpr (EPI != EPI_STORE) {
+    float bias[8];
+    unpack8(*reinterpret_cast<const uint4*>(p.bias + col), bias);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] += bias[e];
+  }
+  if constexpr (EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_RESID_ENCODE) {
+    float a[8];
+    unpack8(*reinterpret_cast<const uint4*>(p.aux + row * p.ldaux + col), a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] += a[e];
+  }
+  if constexpr (EPI == EPI_BIAS_RESID_ENCODE) {
+    // the 8 lanes of a row segment hold one 64-element block; same arithmetic as the one-kernel epilogue
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      x[e] = bf16_bits_to_float(float_to_bf16_bits(x[e]));
+      amax = fmaxf(amax, fabsf(x[e]));
+    }
+    amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+    amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+    amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+    const float sc = amax / 127.0f;
+    uint32_t w[2] = {0u, 0u};
+    if (sc != 0.0f) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float q = fminf(fmaxf(rintf(x[e] / sc), -127.0f), 127.0f);
+        w[e >> 2] |= ((uint32_t)(int)q & 0xFFu) << (8 * (e & 3));
+      }
+    }
+    const size_t e0 = row * p.ldc + col;
+    *reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(p.C) + e0) = make_uint2(w[0], w[1]);
+    if ((col & 63) == 0) p.scales[e0 >> 6] = sc;
+  } else {
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16_raw*>(p.C) + row * p.ldc + col) = pack8_bf16(x);
+  }
+}
+
+// How many parts of K for an [M, N] output of 256 x 256 tiles: as many as keep every workgroup resident at once.
+int splitk_parts_max(int M, int N) {
+  if (M % 256 || N % 256) return 1;
+  const long tiles = (long)(M / 256) * (N / 256);
+  return tiles <= 64 ? 4 : tiles <= 128 ? 2 : 1;
+}
+
 }  // namespace
+
+size_t gemm_splitk_floats(int M, int N) {
+  const int parts = splitk_parts_max(M, N);
+  return parts > 1 ? (size_t)parts * M * N : 0;
+}
 
 // Returns SWARM_ERR_SHAPE when the problem is not tile-aligned (the caller then uses the guarded kernel).
 swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
@@ -295,6 +381,29 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
+  k.ksplit = 1; k.part = nullptr;
+  // Few output tiles, long K, no transposed A (forward and dgrad products of short microbatches): the 256 x 256
+  // tiles at ksplit workgroups per tile fill the chip where 128 x 128 tiles would run at their lower rate.
+  // Every part keeps at least 4096 of K, which is where the second kernel's pass over the partial sums pays.
+  const bool epi_ok = g.epilogue == EPI_STORE || g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_RESID ||
+                      g.epilogue == EPI_BIAS_RESID_ENCODE;
+  if (g.splitk_ws && !g.a_trans && epi_ok && g.N % 64 == 0 && ((uintptr_t)g.splitk_ws & 15) == 0) {
+    int parts = splitk_parts_max(g.M, g.N);
+    while (parts > 1 && (g.K / parts < 4096 || g.K % (parts * DBK))) parts >>= 1;
+    if (parts > 1 && g.splitk_floats >= (size_t)parts * g.M * g.N) {
+      k.ksplit = parts; k.part = g.splitk_ws;
+      k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
+      const swarm_status s = launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);
+      if (s != SWARM_OK) return s;
+      const unsigned blocks = (unsigned)(((size_t)g.M * (g.N / 8) + 255) / 256);
+      if (g.epilogue == EPI_STORE) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE>, dim3(blocks), dim3(256), 0, st, k);
+      else if (g.epilogue == EPI_BIAS) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_BIAS>, dim3(blocks), dim3(256), 0, st, k);
+      else if (g.epilogue == EPI_BIAS_RESID)
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_BIAS_RESID>, dim3(blocks), dim3(256), 0, st, k);
+      else hipLaunchKernelGGL(splitk_reduce_kernel<EPI_BIAS_RESID_ENCODE>, dim3(blocks), dim3(256), 0, st, k);
+      return launch_status();
+    }
+  }
   if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {
     k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
     return launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);

@@ -15,6 +15,18 @@ extern "C" int swarm_kernel_gemm(int dtype, int M, int N, int K, const void* A, 
   return dtype ? gemm_bf16(g, (hipStream_t)stream) : gemm_f32(g, (hipStream_t)stream);
 }
 
+// The same with split-K scratch (floats) that the bf16 kernel may use; swarm_kernel_gemm_splitk_floats says how much.
+extern "C" size_t swarm_kernel_gemm_splitk_floats(int M, int N) { return gemm_splitk_floats(M, N); }
+extern "C" int swarm_kernel_gemm_ws(int M, int N, int K, const void* A, int lda, int a_trans, const void* B, int ldb,
+                                    int b_trans, void* C, int ldc, int epilogue, const void* bias, const void* aux,
+                                    int ldaux, float* scales, float* splitk_ws, size_t splitk_floats, void* stream) {
+  GemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.a_trans = a_trans != 0; g.B = B; g.ldb = ldb;
+  g.b_trans = b_trans != 0; g.C = C; g.ldc = ldc; g.epilogue = epilogue; g.bias = bias; g.aux = aux;
+  g.ldaux = ldaux; g.scales = scales; g.splitk_ws = splitk_ws; g.splitk_floats = splitk_floats;
+  return gemm_bf16(g, (hipStream_t)stream);
+}
+
 extern "C" int swarm_kernel_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H,
                                           int dh, void* stream) {
   return attention_fwd(qkv, o, lse, B, S, H, dh, dtype != 0, (hipStream_t)stream);

@@ -42,7 +42,12 @@ struct GemmArgs {
   const float* rope;       // EPI_BIAS_ROPE: (cos, sin) table [rope_S, rope_dh/2]; row m is at position m % rope_S,
   int rope_S, rope_dh, rope_cols;   // a head spans rope_dh columns, columns >= rope_cols are left alone
   int split;               // EPI_DGEGLU / EPI_BIAS_GEGLU: f, the width of the gate (and of the up) half
+  float* splitk_ws;        // optional scratch of splitk_floats floats (>= gemm_splitk_floats(M, N)): lets a product with
+  size_t splitk_floats;    // few output tiles and a long K be cut along K (bf16 MFMA kernel only); nullptr: never cut
 };
+
+// Floats of split-K scratch that a bf16 product with an [M, N] output can make use of (0: it is never cut).
+size_t gemm_splitk_floats(int M, int N);
 
 // T = float: plain FMA tiles (parity configuration); T = bf16: MFMA kernel.
 swarm_status gemm_f32(const GemmArgs& g, hipStream_t st);

@@ -20,7 +20,16 @@ struct Dims {
   bool rope_geglu;
   bool bf16;
   size_t es;  // element size of the activation dtype
+  float* splitk = nullptr;      // split-K scratch for the bf16 products with few output tiles (set once the
+  size_t splitk_floats = 0;     // workspace is carved)
 };
+
+// split-K scratch that the products of this configuration can use: the widest of their four output shapes
+size_t splitk_floats_of(const Dims& D) {
+  if (!D.bf16) return 0;
+  return std::max(std::max(gemm_splitk_floats(D.T, D.d), gemm_splitk_floats(D.T, 3 * D.d)),
+                  std::max(gemm_splitk_floats(D.T, D.f), gemm_splitk_floats(D.T, D.f1)));
+}
 
 bool valid_config(const swarm_stage_config* c) {
   if (!c) return false;
@@ -82,7 +91,10 @@ void carve_saved(Carver& cv, const Dims& D, Saved& s, bool want_u) {
 }
 
 swarm_status gemm(const Dims& D, const GemmArgs& g, hipStream_t st) {
-  return D.bf16 ? gemm_bf16(g, st) : gemm_f32(g, st);
+  if (!D.bf16) return gemm_f32(g, st);
+  GemmArgs h = g;
+  h.splitk_ws = D.splitk; h.splitk_floats = D.splitk_floats;
+  return gemm_bf16(h, st);
 }
 
 #define SWARM_TRY(expr)                 \
@@ -259,6 +271,7 @@ struct FwdPlan {
   Saved s;
   void* z[2];
   float* rope;
+  float* splitk;
 };
 
 size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
@@ -270,6 +283,7 @@ size_t plan_forward(const Dims& D, void* ws, FwdPlan& P) {
   P.s.rope = P.rope;
   P.z[0] = D.apps > 1 ? cv.take(Td) : nullptr;
   P.z[1] = D.apps > 1 ? cv.take(Td) : nullptr;
+  P.splitk = splitk_floats_of(D) ? (float*)cv.take(splitk_floats_of(D) * 4) : nullptr;
   return cv.total();
 }
 
@@ -287,6 +301,7 @@ struct BwdPlan {
   char *du_slots, *dh_slots, *dqkv_slots;   // [R] slots of [T,f1], [T,d], [T,3d]: one per application of a set
   char* dys[2];              // [R] slots of [T,d] (gradient of each application's output), by parameter-set parity
   float* rope;
+  float* splitk;
 };
 
 size_t plan_backward(const Dims& D, int L, int R, void* ws, BwdPlan& P) {
@@ -320,6 +335,7 @@ size_t plan_backward(const Dims& D, int L, int R, void* ws, BwdPlan& P) {
   size_t pf = layernorm_bwd_scratch_floats(D.T, D.d);
   pf = std::max(pf, colsum_scratch_floats(wgrad_chunk(D, R) * D.T, std::max(3 * D.d, D.f1)));
   P.t.partial = (float*)cv.take(pf * 4);
+  P.splitk = splitk_floats_of(D) ? (float*)cv.take(splitk_floats_of(D) * 4) : nullptr;
   return cv.total();
 }
 
@@ -409,9 +425,10 @@ extern "C" swarm_status swarm_stage_forward(const swarm_stage_config* cfg, const
   if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
   if (!params_ok(params, cfg->n_layers)) return SWARM_ERR_NULL;
   if (x_in == x_out || !aligned16(x_in) || !aligned16(x_out) || ((uintptr_t)workspace & 255)) return SWARM_ERR_SHAPE;
-  const Dims D = dims_of(cfg);
+  Dims D = dims_of(cfg);
   FwdPlan P;
   if (plan_forward(D, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  D.splitk = P.splitk; D.splitk_floats = P.splitk ? splitk_floats_of(D) : 0;
   hipStream_t st = (hipStream_t)hip_stream;
   if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
   const void* cur = x_in;
@@ -438,9 +455,10 @@ extern "C" swarm_status swarm_stage_backward(const swarm_stage_config* cfg, cons
   if (grad_in == grad_out || grad_in == x_in || !aligned16(x_in) || !aligned16(grad_out) || !aligned16(grad_in) ||
       ((uintptr_t)workspace & 255))
     return SWARM_ERR_SHAPE;
-  const Dims D = dims_of(cfg);
+  Dims D = dims_of(cfg);
   BwdPlan P;
   if (plan_backward(D, cfg->n_layers, cfg->n_repeat, workspace, P) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  D.splitk = P.splitk; D.splitk_floats = P.splitk ? splitk_floats_of(D) : 0;
   return run_backward(D, cfg, params, x_in, grad_out, grad_in, nullptr, nullptr, grad_params, P,
                       (hipStream_t)hip_stream);
 }
@@ -472,7 +490,7 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
   if (!aligned16(x_dec) || !aligned16(x_codes) || !aligned16(y_codes) || ((uintptr_t)workspace & 255))
     return SWARM_ERR_SHAPE;
   if (swarm_stage_coded_workspace_bytes(cfg, 0) > workspace_bytes) return SWARM_ERR_WORKSPACE;
-  const Dims D = dims_of(cfg);
+  Dims D = dims_of(cfg);
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t base = swarm_stage_workspace_bytes(cfg, 0);
   void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
@@ -484,6 +502,7 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
   }
   FwdPlan P;
   plan_forward(D, workspace, P);
+  D.splitk = P.splitk; D.splitk_floats = P.splitk ? splitk_floats_of(D) : 0;
   if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
   const void* cur = x_dec;
   int app = 0;
@@ -515,7 +534,7 @@ extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg
   if (!aligned16(x_in) || !aligned16(g_codes) || !aligned16(gin_codes) || ((uintptr_t)workspace & 255))
     return SWARM_ERR_SHAPE;
   if (swarm_stage_coded_workspace_bytes(cfg, 1) > workspace_bytes) return SWARM_ERR_WORKSPACE;
-  const Dims D = dims_of(cfg);
+  Dims D = dims_of(cfg);
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t base = swarm_stage_workspace_bytes(cfg, 1);
   void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
@@ -529,5 +548,6 @@ extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg
   }
   BwdPlan P;
   plan_backward(D, cfg->n_layers, cfg->n_repeat, workspace, P);
+  D.splitk = P.splitk; D.splitk_floats = P.splitk ? splitk_floats_of(D) : 0;
   return run_backward(D, cfg, params, x_in, tmp, nullptr, gin_codes, gin_scales, grad_params, P, st);
 }

@@ -67,8 +67,12 @@ def test_end_to_end_stage_with_codec():
     assert not bad, bad
     assert max_norm_err(full["x_out"][:1], ref0["x_out"]) <= TOL
     assert max_norm_err(full["grad_in"][:1], ref0["grad_in"]) <= TOL
-    # sequences are independent: the full run reproduces the single-sequence run bit for bit
-    assert np.array_equal(full["x_out"][:1], gpu0["x_out"]) and np.array_equal(full["grad_in"][:1], gpu0["grad_in"])
+    # sequences are independent: the full run reproduces the single-sequence run up to the summation order of the
+    # products that the library cuts along K at 2048 rows and does not cut at 8192 (fp32 partial sums, so a few bf16
+    # roundings differ by one unit after two blocks; one bf16 unit of the largest element is 2^-7 of it)
+    SEQ_TOL = 2.0 ** -6
+    assert max_norm_err(full["x_out"][:1], gpu0["x_out"]) <= SEQ_TOL
+    assert max_norm_err(full["grad_in"][:1], gpu0["grad_in"]) <= SEQ_TOL
     # (2) accumulation: full-microbatch gradients = sum over sequences
     tot = [{k: v.copy() for k, v in g.items()} for g in gpu0["grads"]]
     for b in range(1, wl.batch):
@@ -76,10 +80,11 @@ def test_end_to_end_stage_with_codec():
         for l in range(wl.n_layers):
             for k in tot[l]:
                 tot[l][k] += gb["grads"][l][k]
-        assert np.array_equal(full["grad_in"][b:b + 1], gb["grad_in"])
+        assert max_norm_err(full["grad_in"][b:b + 1], gb["grad_in"]) <= SEQ_TOL
     for l in range(wl.n_layers):
         for k in tot[l]:
-            assert max_norm_err(full["grads"][l][k], tot[l][k]) <= 1e-4, (l, k)
+            # (bf16 tolerance: the single-sequence runs cut some products along K, see above)
+            assert max_norm_err(full["grads"][l][k], tot[l][k]) <= TOL, (l, k)
     # (3) stage exit: encode x_out and grad_in on the GPU, bit-exact against the oracle codec on the same bits
     for key in ("x_out", "grad_in"):
         t = torch.from_numpy(full[key].astype(np.float32)).to(torch.bfloat16).cuda()

@@ -94,6 +94,79 @@ def test_gemm_epilogues(epi, shape):
     gemm_case(M, N, K, False, epi == 4, epi, seed=epi)
 
 
+# ------------------------------------------------------------------ split-K
+def _splitk_call(lib, M, N, K, Ad, lda, Bd, ldb, b_t, Cd, epi, bd, xd, scales, ws):
+    lib.swarm_kernel_gemm_ws.restype = C.c_int
+    lib.swarm_kernel_gemm_ws.argtypes = [C.c_int] * 3 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                        C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    st = lib.swarm_kernel_gemm_ws(M, N, K, Ad.data_ptr(), lda, 0, Bd.data_ptr(), ldb, int(b_t), Cd.data_ptr(), N, epi,
+                                  bd.data_ptr(), xd.data_ptr(), N, scales.data_ptr() if scales is not None else None,
+                                  ws.data_ptr() if ws is not None else None, ws.numel() if ws is not None else 0, None)
+    assert st == 0
+    torch.cuda.synchronize()
+
+
+# (M, N, K, parts the kernel takes): one tile cut in four, 16 tiles cut in two (K / 4 would be below 4096),
+# 128 tiles cut in two, and a product that is not cut (K too short) although scratch is offered
+@pytest.mark.parametrize("shape", [(256, 256, 16384), (512, 2048, 8192), (2048, 4096, 8192), (256, 512, 4096)])
+@pytest.mark.parametrize("b_t", [False, True])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_gemm_splitk(shape, b_t, epi):
+    M, N, K = shape
+    lib = _lib()
+    lib.swarm_kernel_gemm_splitk_floats.restype = C.c_size_t
+    nfl = lib.swarm_kernel_gemm_splitk_floats(M, N)
+    assert nfl == (4 if (M // 256) * (N // 256) <= 64 else 2) * M * N
+    seed = M + N + K + epi
+    A = _bf(synth.normal(seed, "A", (M, K)))
+    B = _bf(synth.normal(seed, "B", (K, N) if b_t else (N, K)))
+    bias = _bf(synth.normal(seed, "bias", (N,)))
+    aux = _bf(synth.normal(seed, "aux", (M, N)))
+    ref = A.double().numpy() @ (B.double().numpy() if b_t else B.double().numpy().T)
+    if epi >= 1:
+        ref = ref + bias.double().numpy()
+    if epi == 2:
+        ref = ref + aux.double().numpy()
+    Ad, Bd, bd, xd = A.cuda(), B.cuda(), bias.cuda(), aux.cuda()
+    ws = torch.full((nfl,), float("nan"), dtype=torch.float32, device="cuda")
+    C1 = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, B.shape[1], b_t, C1, epi, bd, xd, None, ws)
+    got = C1.double().cpu().numpy()
+    err = np.max(np.abs(got - ref)) / np.max(np.abs(ref))
+    assert err < 6e-3, err
+    cut = K // 2 >= 4096
+    assert bool(torch.isnan(ws).all()) == (not cut)            # the scratch is used exactly when K is long enough
+    # the one-kernel product of the same operands: equal up to the summation order of the fp32 partial sums, i.e.
+    # at most one bf16 unit (2^-7 of the element) apart after rounding
+    C0 = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, B.shape[1], b_t, C0, epi, bd, xd, None, None)
+    d = np.max(np.abs(C0.double().cpu().numpy() - got)) / np.max(np.abs(ref))
+    assert d <= 2.0 ** -7 and (cut or d == 0.0), d
+
+
+def test_gemm_splitk_encode_equals_encode_of_stored():
+    """EPI 6 (bias + residual, int8-encoded) through the split path: codes and scales are those of the stand-alone
+    codec applied to what the bias + residual epilogue stores (same scratch, same summation order)."""
+    import paper_2301_11913_amd as sw
+    M, N, K = 512, 1024, 8192
+    lib = _lib()
+    A = _bf(synth.normal(3, "A", (M, K))); B = _bf(synth.normal(3, "B", (N, K)))
+    bias = _bf(synth.normal(3, "bias", (N,))); aux = _bf(synth.normal(3, "aux", (M, N)))
+    Ad, Bd, bd, xd = A.cuda(), B.cuda(), bias.cuda(), aux.cuda()
+    lib.swarm_kernel_gemm_splitk_floats.restype = C.c_size_t
+    ws = torch.empty(lib.swarm_kernel_gemm_splitk_floats(M, N), dtype=torch.float32, device="cuda")
+    Cb = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, K, False, Cb, 2, bd, xd, None, ws)
+    codes = torch.empty((M, N), dtype=torch.int8, device="cuda")
+    scales = torch.empty(M * N // 64, dtype=torch.float32, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, K, False, codes, 6, bd, xd, scales, ws)
+    c2 = torch.empty(M * N, dtype=torch.int8, device="cuda"); s2 = torch.empty_like(scales)
+    sw.swarm_codec_encode(Cb.reshape(-1), c2, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(codes.reshape(-1), c2) and torch.equal(scales.view(torch.int32), s2.view(torch.int32))
+
+
 # ------------------------------------------------------------------ attention
 def _attn_lib():
     lib = _lib()
