@@ -220,6 +220,8 @@ bool valid(const swarm_head_config* c) {
 struct Plan {
   void *n, *logits, *dn;
   float *mean, *rstd, *tok, *partial;
+  float* splitk;
+  size_t splitk_floats;
 };
 
 size_t plan(const swarm_head_config* c, bool backward, void* ws, Plan& P) {
@@ -238,10 +240,13 @@ size_t plan(const swarm_head_config* c, bool backward, void* ws, Plan& P) {
   P.rstd = (float*)take(T * 4);
   P.tok = (float*)take(T * 4);
   P.logits = take(T * c->vocab_rows * es);
-  P.dn = nullptr; P.partial = nullptr;
+  P.dn = nullptr; P.partial = nullptr; P.splitk = nullptr; P.splitk_floats = 0;
   if (backward) {
     P.dn = take(T * c->d_model * es);
     P.partial = (float*)take(layernorm_bwd_scratch_floats(c->tokens, c->d_model) * 4);
+    // dn = dlogits W has few output tiles and K = vocabulary rows: scratch for cutting it along K
+    P.splitk_floats = c->dtype == SWARM_BF16 ? gemm_splitk_floats(c->tokens, c->d_model) : 0;
+    if (P.splitk_floats) P.splitk = (float*)take(P.splitk_floats * 4);
   }
   return (off + 255) & ~(size_t)255;
 }
@@ -285,7 +290,7 @@ swarm_status run_head(const swarm_head_config* cfg, const swarm_head_params* p, 
   SWARM_TRY(gemm(bf16, w, st));
   GemmArgs g{};   // dn [T, d] = dlogits W
   g.M = T; g.N = d; g.K = Vp; g.A = P.logits; g.lda = Vp; g.B = p->w_vocab; g.ldb = d; g.b_trans = true; g.C = P.dn;
-  g.ldc = d; g.epilogue = EPI_STORE;
+  g.ldc = d; g.epilogue = EPI_STORE; g.splitk_ws = P.splitk; g.splitk_floats = P.splitk_floats;
   SWARM_TRY(gemm(bf16, g, st));
   return layernorm_bwd(P.dn, x, P.mean, P.rstd, p->ln_g, nullptr, dx, grads->ln_g, grads->ln_b, P.partial, T, d, bf16,
                        st);
