@@ -13,7 +13,9 @@ namespace {
 
 constexpr int kLnThreads = 256;              // 4 wavefronts per workgroup
 constexpr int kLnWaves = kLnThreads / kWave;
-constexpr int kLnRowsPerBlock = 16;          // backward: rows per workgroup
+// backward: rows per workgroup (a multiple of the rows per barrier); fewer for short inputs, so that the launch
+// still has at least two workgroups per compute unit
+static inline int ln_rows_per_block(int T) { return T >= 8192 ? 16 : T >= 4096 ? 8 : 4; }
 
 template <typename T> struct V8;
 template <> struct V8<bf16_raw> {
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
 
 // Backward.  The four wavefronts of a workgroup split the COLUMNS of a row (a quarter each), so a lane
 // carries only d/256 dgamma / dbeta partial sums; the two row statistics are combined across the
-// wavefronts through LDS, four rows per barrier.  A workgroup walks kLnRowsPerBlock rows and writes its
+// wavefronts through LDS, four rows per barrier.  A workgroup walks rpb rows and writes its
 // column partials to partial[gridDim.x][2][d] (dgamma then dbeta); a fixed-order second stage adds them up.
 // ENC: dx leaves int8-encoded (stage-boundary codec): a lane octet holds one 64-element block of the
 // row (needs d % 256 == 0 so that blocks do not straddle wavefronts); the values are rounded to T first,
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
                                                             const T* __restrict__ gamma, const T* __restrict__ dres,
                                                             T* __restrict__ dx, float* __restrict__ partial, int rows,
                                                             int d, int8_t* __restrict__ codes,
-                                                            float* __restrict__ scales) {
+                                                            float* __restrict__ scales, int rpb) {
   __shared__ float red[2][kLnBatch][kLnWaves][2];
   typedef typename V8<T>::Raw Raw;
   const int lane = threadIdx.x & 63;
@@ -166,8 +168,8 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
     for (int i = 0; i < 8; ++i) { pg[it][i] = 0.f; pb[it][i] = 0.f; }
     graw[it] = V8<T>::load_raw(gamma + (size_t)(cbase + (c < cq ? c : 0)) * 8);
   }
-  const int row0 = blockIdx.x * kLnRowsPerBlock;
-  for (int b0 = 0; b0 < kLnRowsPerBlock; b0 += kLnBatch) {
+  const int row0 = blockIdx.x * rpb;
+  for (int b0 = 0; b0 < rpb; b0 += kLnBatch) {
     const int par = (b0 / kLnBatch) & 1;
     Raw xraw[kLnBatch][NITQ], dyraw[kLnBatch][NITQ];
     float mu[kLnBatch], rs[kLnBatch];
@@ -341,10 +343,11 @@ template <typename T, bool ENC>
 swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const float* rstd, const T* g,
                              const T* dres, T* dx, float* partial, int rows, int d, int8_t* codes, float* scales,
                              hipStream_t st) {
-  const int grid = (rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
+  const int rpb = ln_rows_per_block(rows);
+  const int grid = (rows + rpb - 1) / rpb;
 #define LN_BWD(NITQ)                                                                                             \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ, ENC>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
-                     dres, dx, partial, rows, d, codes, scales)
+                     dres, dx, partial, rows, d, codes, scales, rpb)
   if (d <= 2048) LN_BWD(1);
   else if (d <= 4096) LN_BWD(2);
   else if (d <= 8192) LN_BWD(4);
@@ -375,7 +378,8 @@ swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void
 }
 
 size_t layernorm_bwd_scratch_floats(int T, int d) {
-  return (size_t)((T + kLnRowsPerBlock - 1) / kLnRowsPerBlock) * 2 * d;
+  const int rpb = ln_rows_per_block(T);
+  return (size_t)((T + rpb - 1) / rpb) * 2 * d;
 }
 
 // codes != nullptr: dx is not written; its int8 encoding goes to codes / scales (needs d % 256 == 0)
@@ -396,7 +400,7 @@ swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, con
               : ln_bwd_dispatch<float, false>(a, b, mean, rstd, g, r, (float*)dx, partial, T, d, nullptr, nullptr, st);
   }
   if (s != SWARM_OK) return s;
-  const int P = (T + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
+  const int P = (T + ln_rows_per_block(T) - 1) / ln_rows_per_block(T);
   const int grid = (d + 63) / 64;
   hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid), dim3(256), 0, st, partial, P, d, (size_t)2 * d, dgamma);
   hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid), dim3(256), 0, st, partial + d, P, d, (size_t)2 * d,
