@@ -20,7 +20,9 @@
  *   - errors that the host can see (null pointer, unsupported shape, small
  *     workspace) return a negative status BEFORE anything is launched and leave
  *     all outputs untouched; a failed launch returns SWARM_ERR_LAUNCH;
- *   - results are bitwise reproducible from call to call (no float atomics).
+ *   - results are bitwise reproducible from call to call (no float atomics); which
+ *     kernels run depends on the shapes, so the same rows inside a microbatch of
+ *     another size agree to the rounding of the dtype, not bit for bit;
  *   - all matrices are row-major with the last index contiguous.
  */
 #ifndef SWARM_STAGE_H
