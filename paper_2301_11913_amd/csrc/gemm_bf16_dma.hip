@@ -15,6 +15,7 @@
 //                                          banks, so 32-byte pairs are XOR-ed with 2*(k-row & 3).
 //
 // One workgroup owns one output tile and walks K in order: deterministic.
+#include <algorithm>
 #include <cstdlib>
 
 #include "gemm_bf16_common.h"
@@ -402,6 +403,34 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
         hipLaunchKernelGGL(splitk_reduce_kernel<EPI_BIAS_RESID>, dim3(blocks), dim3(256), 0, st, k);
       else hipLaunchKernelGGL(splitk_reduce_kernel<EPI_BIAS_RESID_ENCODE>, dim3(blocks), dim3(256), 0, st, k);
       return launch_status();
+    }
+  }
+  // A tile count that leaves the last round of 256 workgroups at most half full (384 tiles = 1.5 rounds for the
+  // QKV product of a 2048-row microbatch): the columns that make whole rounds go first, the rest is a product of
+  // its own (smaller tiles or a cut along K fill the chip there).  Column-local epilogues only.
+  if (!g.a_trans && g.M % 256 == 0 && g.N % 256 == 0 &&
+      (g.epilogue == EPI_STORE || g.epilogue == EPI_BIAS || g.epilogue == EPI_BIAS_RESID ||
+       g.epilogue == EPI_BIAS_GELU || g.epilogue == EPI_DGELU || g.epilogue == EPI_BIAS_ROPE)) {
+    const long tm = g.M / 256, tn = g.N / 256, tiles = tm * tn;
+    const long whole = (tiles / 256) * 256;
+    if (tiles > 256 && tiles - whole > 0 && tiles - whole <= 128 && whole % tm == 0) {
+      const int n1 = (int)(whole / tm) * 256;
+      GemmArgs a = g, r = g;
+      a.N = n1;
+      r.N = g.N - n1;
+      r.B = (const bf16_raw*)g.B + (g.b_trans ? (size_t)n1 : (size_t)n1 * g.ldb);
+      r.C = (bf16_raw*)g.C + n1;
+      if (g.bias) r.bias = (const bf16_raw*)g.bias + n1;
+      if (g.aux) r.aux = (const bf16_raw*)g.aux + n1;
+      if (g.C2) r.C2 = (bf16_raw*)g.C2 + n1;
+      if (g.epilogue == EPI_BIAS_ROPE) {
+        a.rope_cols = std::min(g.rope_cols, n1);
+        r.rope_cols = g.rope_cols - n1;
+        if (r.rope_cols <= 0) { r.rope_cols = 0; r.epilogue = EPI_BIAS; }
+      }
+      const swarm_status s = gemm_bf16_dma(a, st);
+      if (s != SWARM_OK) return s;
+      return gemm_bf16_dma(r, st);
     }
   }
   if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {

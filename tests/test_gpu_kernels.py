@@ -145,6 +145,16 @@ def test_gemm_splitk(shape, b_t, epi):
     assert d <= 2.0 ** -7 and (cut or d == 0.0), d
 
 
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("b_t", [False, True])
+def test_gemm_ragged_last_round(epi, b_t):
+    """384 tiles of 256 x 256 (one and a half rounds of the 256 compute units): the columns of the whole round and
+    the remaining columns run as two products; every output column must come out as from one."""
+    if epi == 4 and not b_t or epi in (1, 2, 3) and b_t:
+        pytest.skip("layouts as the stage uses them")
+    gemm_case(2048, 12288, 256, False, b_t, epi, seed=40 + epi)
+
+
 def test_gemm_splitk_encode_equals_encode_of_stored():
     """EPI 6 (bias + residual, int8-encoded) through the split path: codes and scales are those of the stand-alone
     codec applied to what the bias + residual epilogue stores (same scratch, same summation order)."""
