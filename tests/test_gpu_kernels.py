@@ -145,13 +145,11 @@ def test_gemm_splitk(shape, b_t, epi):
     assert d <= 2.0 ** -7 and (cut or d == 0.0), d
 
 
-@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
-@pytest.mark.parametrize("b_t", [False, True])
+@pytest.mark.parametrize("epi,b_t", [(0, False), (0, True), (1, False), (2, False), (3, False), (4, True)])
 def test_gemm_ragged_last_round(epi, b_t):
     """384 tiles of 256 x 256 (one and a half rounds of the 256 compute units): the columns of the whole round and
-    the remaining columns run as two products; every output column must come out as from one."""
-    if epi == 4 and not b_t or epi in (1, 2, 3) and b_t:
-        pytest.skip("layouts as the stage uses them")
+    the remaining columns run as two products; every output column must come out as from one.  Epilogues with the
+    layouts the stage uses them with."""
     gemm_case(2048, 12288, 256, False, b_t, epi, seed=40 + epi)
 
 
