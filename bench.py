@@ -129,7 +129,7 @@ def bench_boundary(args):
         tot_ms += ms.value; tot_fl += fl.value; launches += nl
     lib.swarm_kernel_timing_enable(0)
     achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
                 "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
@@ -213,7 +213,7 @@ def bench_head(args):
         tot_ms += ms.value; tot_fl += fl.value; launches += nl
     lib.swarm_kernel_timing_enable(0)
     achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
                 "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
@@ -428,7 +428,7 @@ def main():
             tot_ms += ms.value; tot_fl += fl.value; launches += nl
         lib.swarm_kernel_timing_enable(0)
         achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dma_kernel", "achieved": round(achieved, 1),
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
                     "avg_launch_us": round(tot_ms * 1e3 / launches, 1),

@@ -71,8 +71,36 @@ __device__ __forceinline__ uint4 pack8_bf16(const float (&x)[8]) {
   return make_uint4(cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3]), cvt_pk_bf16(x[4], x[5]), cvt_pk_bf16(x[6], x[7]));
 }
 
-template <int FM, int FN, bool GUARD>
-__device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][FN], int row0, int col0, int l32,
+// Rows 32 i .. 32 i + 31 of a wavefront's accumulator sub-tile into its LDS patch (row-major, pitch kEpiPitch).
+// 32 x 32 blocks: acc[i][j][r] is the element (8 (r / 4) + 4 lg + r % 4, 32 j + l32) of row group i.
+template <int FM, int FN>
+__device__ __forceinline__ void stage_rows32(const f32x16 (&acc)[FM][FN], int i, float* stage, int lane) {
+  const int l32 = lane & 31, lg = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+}
+// 16 x 16 blocks (v_mfma_f32_16x16x32): blk[i16][j16][r] is the element (4 (lane / 16) + r, lane % 16) of block
+// (i16, j16); a 32-row group holds the block rows 2 i and 2 i + 1.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+template <int FM, int FN>
+struct Acc16 {
+  f32x4 blk[2 * FM][2 * FN];
+};
+template <int FM, int FN>
+__device__ __forceinline__ void stage_rows32(const Acc16<FM, FN>& acc, int i, float* stage, int lane) {
+  const int l16 = lane & 15, q = lane >> 4;
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int j = 0; j < 2 * FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) stage[(16 * h + 4 * q + r) * kEpiPitch + 16 * j + l16] = acc.blk[2 * i + h][j][r];
+}
+
+template <int FM, int FN, bool GUARD, typename Acc>
+__device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, int row0, int col0, int l32,
                                               int lg, float* stage) {
   static_assert(32 * FN <= kEpiPitch - 4, "the LDS patch holds 64 columns");
   const int epi = p.epilogue;
@@ -87,11 +115,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
     const bool colf_ok = !GUARD || colf < p.N;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+      stage_rows32<FM, FN>(acc, i, stage, lane);
 #pragma unroll
       for (int ps = 0; ps < 32 / RPP4; ++ps) {
         const int rl = ps * RPP4 + rsub4;
@@ -120,11 +144,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
     bf16_raw* G = reinterpret_cast<bf16_raw*>(p.C);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+      stage_rows32<FM, FN>(acc, i, stage, lane);
 #pragma unroll
       for (int ps = 0; ps < 2; ++ps) {
         const int rl = ps * 16 + rsub;
@@ -161,11 +181,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, f32x16 (&acc)[FM][
   bf16_raw* C = reinterpret_cast<bf16_raw*>(p.C);
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * lg + (r & 3)) * kEpiPitch + 32 * j + l32] = acc[i][j][r];
+    stage_rows32<FM, FN>(acc, i, stage, lane);
 #pragma unroll
     for (int ps = 0; ps < 32 / RPP; ++ps) {
       const int rl = ps * RPP + rsub;

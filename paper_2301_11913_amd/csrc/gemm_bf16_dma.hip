@@ -17,6 +17,8 @@
 // One workgroup owns one output tile and walks K in order: deterministic.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
+#include <utility>
 
 #include "gemm_bf16_common.h"
 
@@ -33,6 +35,16 @@ constexpr int KCH = DBK / 8;   // 16-byte chunks per row of a non-transposed til
 // hit 16 distinct 16-byte bank groups
 __device__ __forceinline__ int swz_rows(int row) {
   return DBK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3);
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -273,10 +285,207 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
                                reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The same product on v_mfma_f32_16x16x32_bf16.  A loop of nothing but MFMAs on random operands sustains 5-12 %
+// more flops with the 16 x 16 x 32 shape than with 32 x 32 x 16 (the chip is power-limited there), and this kernel
+// keeps that margin.  Per 32-deep sub-step a wavefront holds WTM/16 A fragments (16 rows x 32 k, 8 k-values per
+// lane: lane % 16 -> row, lane / 16 -> k quarter) and WTN/16 B fragments; the MFMAs go row by row, and the A
+// fragment of a row is re-read for the next sub-step as soon as the row is done (single buffer), the B fragments
+// alternate between two buffers.  Two sub-steps per 64-deep slice; the second starts with one row of MFMAs, then
+// the per-slice load wait and barrier, then the reads of the next slice and the refill of the freed stage.
+
+// 16 rows x 32 k fragment of a non-transposed tile (rows of DBK k)
+__device__ __forceinline__ bf16x8 frag_rows16(const bf16_raw* tile, int row_base, int kk, int l16, int q) {
+  const int row = row_base + l16;
+  const int chunk = (4 * kk + q) ^ swz_rows(l16);
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + row * DBK + chunk * 8));
+}
+// the same fragment from a [k][BR] tile through the LDS transpose read (two plain instructions, caller waits)
+template <int BR>
+__device__ __forceinline__ bf16x8 frag_trans16(const bf16_raw* tile, int col_base, int kk, int lane) {
+  const int l16 = lane & 15, q = lane >> 4;
+  const int col = col_base + 4 * (l16 & 3);
+  const int kq = l16 >> 2;                                   // k-row inside the group of four
+  const int chunk = (col >> 3) ^ (4 * kq);
+  const int off = chunk * 8 + (col & 4);
+  const int krow = 32 * kk + 8 * q + kq;
+  const bf16_raw* p0 = tile + krow * BR + off;
+  const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p0;
+  uint2 a, b;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(a) : "v"(addr) : "memory");
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(b) : "v"(addr), "n"(8 * BR) : "memory");
+  return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
+}
+
+// Which fragment of the NEXT sub-step is requested behind MFMA slot n (slot = 4 * row + column): 0 .. FM-1 = A row,
+// FM + j = B column j, -1 = none.  kind 0: a sub-step without barrier; kind 1: barrier behind slot 3, nothing of
+// the next slice may be read before it.
+template <int FM, int FN>
+constexpr int k32_read_at(int kind, int n) {
+  if (n % FN == FN - 1 && n / FN >= 1) return n / FN;                      // A_i behind the last MFMA of row i >= 1
+  if (kind == 0) {
+    if (n == FN - 1) return 0;                                             // A_0 behind the last MFMA of row 0
+    if (n % FN == 1 && n / FN < FN) return FM + n / FN;                    // B_j behind slot FN * j + 1
+  } else {
+    if (n == FN) return 0;                                                 // A_0 behind the first MFMA after the barrier
+    if (n % FN == 1 && n / FN >= 1 && n / FN <= FN) return FM + n / FN - 1;  // B_j behind slot FN * (j + 1) + 1
+  }
+  return -1;
+}
+// LDS read instructions younger than the fragment(s) that row i of a sub-step of kind `cur` needs (A_i; for i = 0
+// also every B), `prev` being the kind of the sub-step before it; ia / ib = instructions per A / B fragment
+template <int FM, int FN>
+constexpr int k32_younger(int prev, int cur, int i, int ia, int ib) {
+  int needed = -1;
+  for (int n = 0; n < FM * FN; ++n) {
+    const int f = k32_read_at<FM, FN>(prev, n);
+    if (f == i || (i == 0 && f >= FM)) needed = n > needed ? n : needed;
+  }
+  int cnt = 0;
+  for (int n = needed + 1; n < FM * FN; ++n) {
+    const int f = k32_read_at<FM, FN>(prev, n);
+    if (f >= 0) cnt += f < FM ? ia : ib;
+  }
+  for (int n = 0; n < FN * i; ++n) {
+    const int f = k32_read_at<FM, FN>(cur, n);
+    if (f >= 0) cnt += f < FM ? ia : ib;
+  }
+  return cnt > 15 ? 15 : cnt;
+}
+
+template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
+  constexpr int NW = WM * WN;
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int FM = WTM / 16, FN = WTN / 16;
+  constexpr int STAGE = (BM + BN) * DBK;              // elements
+  constexpr int IPW = (BM + BN) * DBK / 512 / NW;       // load instructions per wavefront per stage
+  constexpr int IPA = BM * DBK / 512 / NW;
+  static_assert(DBK == 64 && NS == 2, "two 32-deep sub-steps per slice, two stages");
+  static_assert(FN >= 2 && FM >= FN + 1 && 2 * IPW + FN + 2 <= FM * FN, "read / load slots of a sub-step");
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+
+  int tile_m, tile_n;
+  if (p.ksplit > 1) {
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int part = blockIdx.x / ntiles;
+    tile_of_block(p, tile_m, tile_n, blockIdx.x - part * ntiles);
+    p.K /= p.ksplit;
+    p.A += A_T ? (size_t)part * p.K * p.lda : (size_t)part * p.K;
+    p.B += B_T ? (size_t)part * p.K * p.ldb : (size_t)part * p.K;
+    p.C = p.part + (size_t)part * p.M * p.N;
+    p.ldc = p.N;
+    p.epilogue = EPI_PART_F32;
+  } else {
+    tile_of_block(p, tile_m, tile_n);
+  }
+  const int m0 = tile_m * BM;
+  const int glu = (!B_T && p.epilogue == EPI_BIAS_GEGLU) ? p.split : 0;
+  const int n0 = glu ? tile_n * (BN / 2) : tile_n * BN;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int l16 = lane & 15, q = lane >> 4;
+
+  Acc16<WTM / 32, WTN / 32> acc;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc.blk[i][j][r] = 0.f;
+
+  const int KT = p.K / DBK;
+  issue_tile<BM, NW, A_T>(p.A, p.lda, m0, 0, lds, wave, lane);
+  issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, 0, lds + BM * DBK, wave, lane, glu);
+  {
+    const int k1 = min(1, KT - 1) * DBK;
+    issue_tile<BM, NW, A_T>(p.A, p.lda, m0, k1, lds + STAGE, wave, lane);
+    issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, k1, lds + STAGE + BM * DBK, wave, lane, glu);
+  }
+  wait_vmcnt<IPW>();
+  __builtin_amdgcn_s_barrier();
+
+  auto read_a = [&](const bf16_raw* sA, int i, int kk) __attribute__((always_inline)) {
+    if constexpr (A_T) return frag_trans16<BM>(sA, wm * WTM + 16 * i, kk, lane);
+    else return frag_rows16(sA, wm * WTM + 16 * i, kk, l16, q);
+  };
+  auto read_b = [&](const bf16_raw* sA, int j, int kk) __attribute__((always_inline)) {
+    const bf16_raw* sB = sA + BM * DBK;
+    if constexpr (B_T) return frag_trans16<BN>(sB, wn * WTN + 16 * j, kk, lane);
+    else return frag_rows16(sB, wn * WTN + 16 * j, kk, l16, q);
+  };
+  bf16x8 fa[FM], fb[2][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) fa[i] = read_a(lds, i, 0);
+#pragma unroll
+  for (int j = 0; j < FN; ++j) fb[0][j] = read_b(lds, j, 0);
+  lds_reads_done();
+
+  constexpr int IA = A_T ? 2 : 1, IB = B_T ? 2 : 1;
+  // One sub-step: FM * FN MFMAs on (fa, cb); behind them the reads of the next sub-step's fragments from the tile
+  // at nA, sub-step nkk (A in place, B into nb).  KIND 1: the per-slice wait and barrier sit behind the first row,
+  // and the loads of slice lk go into stage ls behind the MFMAs that follow it.
+  auto substep = [&](auto kind_c, const bf16x8 (&cb)[FN], bf16x8 (&nb)[FN], const bf16_raw* nA, int nkk, int lk,
+                     int ls) __attribute__((always_inline)) {
+    constexpr int KIND = decltype(kind_c)::value;
+    bf16_raw* st = lds + ls * STAGE;
+    static_for<FM * FN>([&](auto nc) __attribute__((always_inline)) {
+      constexpr int n = decltype(nc)::value;
+      constexpr int i = n / FN, j = n % FN;
+      if constexpr (j == 0 && (A_T || B_T)) {
+        // fragments requested with plain instructions: wait until A_i (row 0: and every B) has arrived
+        constexpr int younger = k32_younger<FM, FN>(1 - KIND, KIND, i, IA, IB);
+        __builtin_amdgcn_s_waitcnt(0xC07F | (younger << 8));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (KIND == 1 && n == FN) {
+        // slice kt+1 must have landed (this wavefront's part) and this wavefront's reads of slice kt be complete;
+        // then all wavefronts meet
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+      }
+      acc.blk[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], cb[j], acc.blk[i][j], 0, 0, 0);
+      constexpr int f = k32_read_at<FM, FN>(KIND, n);
+      if constexpr (f >= 0 && f < FM) fa[f] = read_a(nA, f, nkk);
+      if constexpr (f >= FM) nb[f - FM] = read_b(nA, f - FM, nkk);
+      if constexpr (KIND == 1 && n >= FN + 2 && (n - FN) % 2 == 0 && (n - FN - 2) / 2 < IPW) {
+        constexpr int t = (n - FN - 2) / 2;
+        if constexpr (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+        else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  for (int kt = 0; kt < KT; ++kt) {
+    const bf16_raw* sA = lds + (kt & 1) * STAGE;
+    const bf16_raw* nA = lds + ((kt + 1) & 1) * STAGE;
+    substep(std::integral_constant<int, 0>{}, fb[0], fb[1], sA, 1, 0, 0);
+    // the stage of slice kt is free behind the barrier (the last iterations re-fetch the last slice instead of
+    // branching)
+    substep(std::integral_constant<int, 1>{}, fb[1], fb[0], nA, 0, min(kt + 2, KT - 1), kt & 1);
+  }
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read: the stages become epilogue patches
+
+  gemm_epilogue<WTM / 32, WTN / 32, false>(p, acc, m0 + wm * WTM, glu ? n0 + wn * (WTN / 2) : n0 + wn * WTN,
+                                          lane & 31, lane >> 5,
+                                          reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
+}
+
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
 swarm_status launch_dma(const KArgs& k, hipStream_t st) {
   constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * DBK * sizeof(bf16_raw);
-  auto kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, A_T, B_T>;
+#ifndef SWARM_GEMM_K32
+#define SWARM_GEMM_K32 1
+#endif
+  // 256 x 256 tiles: the 16 x 16 x 32 kernel; the 128 x 128 tile stays on 32 x 32 x 16 (measured 2 % faster there)
+  void (*kern)(KArgs);
+  if constexpr (SWARM_GEMM_K32 && BM == 256) kern = gemm_bf16_k32_kernel<BM, BN, WM, WN, A_T, B_T>;
+  else kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, A_T, B_T>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
