@@ -65,3 +65,31 @@ def test_lamb_is_reproducible():
     a = _run(300001, 2, seed=9)
     b = _run(300001, 2, seed=9)
     assert torch.equal(a, b)
+
+
+@pytest.mark.timeout(600)
+def test_lamb_largest_tensor_of_the_bench_workload():
+    """The launch configuration bench.py times: w_1 of the Section 4.3 stage (134 M elements), two steps, every
+    element against the oracle."""
+    import swarm_synth as synth
+    import paper_2301_11913_amd as sw
+    wl = synth.LAMB_WORKLOADS["lamb_stage_rope_geglu_d4096"]
+    big = max(range(len(wl.shapes)), key=lambda i: int(np.prod(wl.shapes[i])))
+    w0, g = synth.make_lamb_tensor(wl, big)
+    n = w0.size
+    assert n == 32768 * 4096
+    wd, gd = torch.from_numpy(w0).cuda(), torch.from_numpy(g).cuda()
+    md, vd = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    pd = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(sw.swarm_lamb_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ratio = torch.zeros(1, device="cuda")
+    w, m, v = w0, np.zeros(n), np.zeros(n)
+    for t in (1, 2):
+        sw.swarm_lamb_step(wd, pd, gd, md, vd, t, ws, trust_ratio=ratio)
+        torch.cuda.synchronize()
+        w, m, v, r = lamb_step(w, g, m, v, t)
+        assert abs(ratio.item() - r) <= 1e-5 * r
+        for got, ref in ((wd, w), (md, m), (vd, v)):
+            d = np.abs(got.cpu().numpy().astype(np.float64) - ref).max()
+            assert d <= 1e-5 * np.abs(ref).max(), t
+        assert torch.equal(pd, wd.to(torch.bfloat16))
