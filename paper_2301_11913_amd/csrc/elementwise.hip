@@ -295,9 +295,12 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
 }
 
 // Stage 2: out[c] += sum_p partial[p*stride + c], p ascending.  Workgroup = 64 columns x 4 row groups.
+// blockIdx.y = 1 (LayerNorm backward: dbeta next to dgamma in one launch) takes partial + C and out2.
 __global__ __launch_bounds__(256) void reduce_rows_accum_kernel(const float* __restrict__ partial, int P, int C,
-                                                                size_t stride, float* __restrict__ out) {
+                                                                size_t stride, float* __restrict__ out,
+                                                                float* __restrict__ out2) {
   __shared__ float red[4][64];
+  if (blockIdx.y == 1) { partial += C; out = out2; }
   const int c = blockIdx.x * 64 + (threadIdx.x & 63);
   const int rg = threadIdx.x >> 6;
   const int per = (P + 3) / 4;
@@ -402,8 +405,7 @@ swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, con
   if (s != SWARM_OK) return s;
   const int P = (T + ln_rows_per_block(T) - 1) / ln_rows_per_block(T);
   const int grid = (d + 63) / 64;
-  hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid), dim3(256), 0, st, partial, P, d, (size_t)2 * d, dgamma);
-  hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid), dim3(256), 0, st, partial + d, P, d, (size_t)2 * d,
+  hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid, 2), dim3(256), 0, st, partial, P, d, (size_t)2 * d, dgamma,
                      dbeta);
   return launch_status();
 }
@@ -418,7 +420,7 @@ swarm_status colsum_accum(const void* X, int T, int N, float* out, float* partia
   else
     hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, st, (const float*)X, T, N, partial);
   hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3((N + 63) / 64), dim3(256), 0, st, partial, P, N, (size_t)N,
-                     out);
+                     out, (float*)nullptr);
   return launch_status();
 }
 
