@@ -82,6 +82,12 @@ extern "C" swarm_status swarm_compress_forward(const swarm_boundary_config* cfg,
   hipStream_t st = (hipStream_t)hip_stream;
   const bool bf16 = cfg->dtype == SWARM_BF16;
   const int T = cfg->tokens, m = cfg->d_model, c = cfg->d_comp;
+  if (!bottleneck) {
+    // windows of 2, 4 or 8 lie inside one lane's 8 values: LayerNorm and maxout in one kernel
+    const swarm_status fused = layernorm_fwd_maxout(y, p->ln_g, p->ln_b, z, P.mean, P.rstd, T, m, m / c, cfg->ln_eps,
+                                                    bf16, st);
+    if (fused != SWARM_ERR_SHAPE) return fused;
+  }
   SWARM_TRY(layernorm_fwd(y, p->ln_g, p->ln_b, P.a, P.mean, P.rstd, T, m, cfg->ln_eps, bf16, st));
   if (!bottleneck) return maxout_fwd(P.a, z, T, c, m / c, bf16, st);
   GemmArgs g{};
@@ -105,6 +111,12 @@ extern "C" swarm_status swarm_compress_backward(const swarm_boundary_config* cfg
   hipStream_t st = (hipStream_t)hip_stream;
   const bool bf16 = cfg->dtype == SWARM_BF16;
   const int T = cfg->tokens, m = cfg->d_model, c = cfg->d_comp;
+  if (!bottleneck && (m / c == 2 || m / c == 4 || m / c == 8)) {
+    // fused: statistics, then the LayerNorm backward that rebuilds the normalised row and routes dz itself
+    SWARM_TRY(layernorm_fwd_maxout(y, p->ln_g, p->ln_b, nullptr, P.mean, P.rstd, T, m, -1, cfg->ln_eps, bf16, st));
+    return layernorm_bwd_maxout(dz, y, P.mean, P.rstd, p->ln_g, p->ln_b, dy, grads->ln_g, grads->ln_b, P.partial, T, m,
+                                m / c, bf16, st);
+  }
   SWARM_TRY(layernorm_fwd(y, p->ln_g, p->ln_b, P.a, P.mean, P.rstd, T, m, cfg->ln_eps, bf16, st));
   if (bottleneck) {
     GemmArgs w{};   // dW_c [c, m] += dz^T a

@@ -22,6 +22,10 @@ template <> struct V8<bf16_raw> {
   struct Raw { uint4 v; };                   // 8 elements as loaded (keeps register use low)
   static __device__ __forceinline__ float rounded(float x) { return bf16_bits_to_float(float_to_bf16_bits(x)); }
   static __device__ __forceinline__ Raw load_raw(const bf16_raw* p) { return Raw{*reinterpret_cast<const uint4*>(p)}; }
+  static __device__ __forceinline__ Raw make_raw(const float (&x)[8]) {
+    return Raw{make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
+                          pack_bf16x2(x[6], x[7]))};
+  }
   static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
     const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
 #pragma unroll
@@ -52,6 +56,9 @@ template <> struct V8<float> {
   static __device__ __forceinline__ Raw load_raw(const float* p) {
     return Raw{*reinterpret_cast<const float4*>(p), *reinterpret_cast<const float4*>(p + 4)};
   }
+  static __device__ __forceinline__ Raw make_raw(const float (&x)[8]) {
+    return Raw{make_float4(x[0], x[1], x[2], x[3]), make_float4(x[4], x[5], x[6], x[7])};
+  }
   static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
     x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w; x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
   }
@@ -66,11 +73,52 @@ template <> struct V8<float> {
   }
 };
 
+// n = 1, 2 or 4 consecutive elements of type T from floats (the maxout outputs of one 8-element chunk)
+template <typename T, int N>
+__device__ __forceinline__ void store_small(T* p, const float (&x)[8]) {
+  if constexpr (sizeof(T) == 2) {
+    if constexpr (N == 4) *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
+    else if constexpr (N == 2) *reinterpret_cast<uint32_t*>(p) = pack_bf16x2(x[0], x[1]);
+    else *p = (T)float_to_bf16_bits(x[0]);
+  } else {
+    if constexpr (N == 4) *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    else if constexpr (N == 2) *reinterpret_cast<float2*>(p) = make_float2(x[0], x[1]);
+    else *p = x[0];
+  }
+}
+template <typename T, int N>
+__device__ __forceinline__ void load_small(const T* p, float (&x)[8]) {
+  if constexpr (sizeof(T) == 2) {
+    if constexpr (N == 4) {
+      const uint2 v = *reinterpret_cast<const uint2*>(p);
+      x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xFFFF0000u);
+      x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xFFFF0000u);
+    } else if constexpr (N == 2) {
+      const uint32_t v = *reinterpret_cast<const uint32_t*>(p);
+      x[0] = __uint_as_float(v << 16); x[1] = __uint_as_float(v & 0xFFFF0000u);
+    } else {
+      x[0] = __uint_as_float((uint32_t)*p << 16);
+    }
+  } else {
+    if constexpr (N == 4) { const float4 v = *reinterpret_cast<const float4*>(p); x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w; }
+    else if constexpr (N == 2) { const float2 v = *reinterpret_cast<const float2*>(p); x[0] = v.x; x[1] = v.y; }
+    else x[0] = *p;
+  }
+}
+// The normalised, scaled and shifted value as the fused LayerNorm + maxout kernels (forward and backward) both
+// compute it, rounded to T: the window maxima are decided on exactly these numbers on both sides.
+template <typename T>
+__device__ __forceinline__ float ln_affine_rounded(float v, float mu, float r, float g, float b) {
+  return V8<T>::rounded(__builtin_fmaf((v - mu) * r, g, b));
+}
+
 // NIT = chunks per lane held in registers (d <= NIT * 512).
+// MAXK = 2, 4, 8: the output is maxout_MAXK of the normalised row (y is then [rows, d / MAXK]; the normalised row
+// itself is not stored); MAXK = -1: statistics only.
 // DEC: the input row arrives as int8 codes + one fp32 scale per 64 elements (stage-boundary codec); the
 // decoded row (code * scale rounded to T, exactly what the stand-alone decode kernel writes) is stored to
 // xdec and normalised.
-template <typename T, int NIT, bool DEC>
+template <typename T, int NIT, bool DEC, int MAXK = 0>
 __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                             const T* __restrict__ beta, T* __restrict__ y,
                                                             float* __restrict__ mean, float* __restrict__ rstd,
@@ -119,17 +167,39 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
     }
     const float var = wave_sum(q) * inv_d;
     const float r = 1.0f / sqrtf(var + eps);
-    T* yr = y + (size_t)row * d;
+    if constexpr (MAXK == 0) {
+      T* yr = y + (size_t)row * d;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int c = lane + it * 64;
-      if (c < nchunk) {
-        float g[8], b[8], o[8];
-        V8<T>::load(gamma + c * 8, g);
-        V8<T>::load(beta + c * 8, b);
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + it * 64;
+        if (c < nchunk) {
+          float g[8], b[8], o[8];
+          V8<T>::load(gamma + c * 8, g);
+          V8<T>::load(beta + c * 8, b);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = (v[it][i] - mu) * r * g[i] + b[i];
-        V8<T>::store(yr + c * 8, o);
+          for (int i = 0; i < 8; ++i) o[i] = (v[it][i] - mu) * r * g[i] + b[i];
+          V8<T>::store(yr + c * 8, o);
+        }
+      }
+    } else if constexpr (MAXK > 0) {
+      T* zr = y + (size_t)row * (d / MAXK);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + it * 64;
+        if (c < nchunk) {
+          float g[8], b[8], o[8];
+          V8<T>::load(gamma + c * 8, g);
+          V8<T>::load(beta + c * 8, b);
+#pragma unroll
+          for (int w = 0; w < 8 / MAXK; ++w) {
+            float m = ln_affine_rounded<T>(v[it][w * MAXK], mu, r, g[w * MAXK], b[w * MAXK]);
+#pragma unroll
+            for (int i = 1; i < MAXK; ++i)
+              m = fmaxf(m, ln_affine_rounded<T>(v[it][w * MAXK + i], mu, r, g[w * MAXK + i], b[w * MAXK + i]));
+            o[w] = m;
+          }
+          store_small<T, 8 / MAXK>(zr + c * (8 / MAXK), o);
+        }
       }
     }
     if (lane == 0) { mean[row] = mu; rstd[row] = r; }
@@ -144,14 +214,17 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
 // row (needs d % 256 == 0 so that blocks do not straddle wavefronts); the values are rounded to T first,
 // so codes and scales equal those of the stand-alone encode kernel on the stored dx.
 constexpr int kLnBatch = 4;                  // rows per barrier
-template <typename T, int NITQ, bool ENC>
+// MAXK = 2, 4, 8: dy is the gradient of maxout_MAXK of the normalised row ([rows, d / MAXK]); the normalised row is
+// recomputed from x (beta is needed for that) and each window's gradient goes to its first maximum.
+template <typename T, int NITQ, bool ENC, int MAXK = 0>
 __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                             const float* __restrict__ mean,
                                                             const float* __restrict__ rstd,
                                                             const T* __restrict__ gamma, const T* __restrict__ dres,
                                                             T* __restrict__ dx, float* __restrict__ partial, int rows,
                                                             int d, int8_t* __restrict__ codes,
-                                                            float* __restrict__ scales, int rpb) {
+                                                            float* __restrict__ scales, int rpb,
+                                                            const T* __restrict__ beta = nullptr) {
   __shared__ float red[2][kLnBatch][kLnWaves][2];
   typedef typename V8<T>::Raw Raw;
   const int lane = threadIdx.x & 63;
@@ -159,7 +232,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
   const int cq = d >> 5;                       // chunks per wavefront (a quarter of d/8)
   const int cbase = wave * cq;
   const float inv_d = 1.0f / (float)d;
-  Raw graw[NITQ];
+  Raw graw[NITQ], braw[MAXK > 0 ? NITQ : 1];
   float pg[NITQ][8], pb[NITQ][8];
 #pragma unroll
   for (int it = 0; it < NITQ; ++it) {
@@ -167,6 +240,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
 #pragma unroll
     for (int i = 0; i < 8; ++i) { pg[it][i] = 0.f; pb[it][i] = 0.f; }
     graw[it] = V8<T>::load_raw(gamma + (size_t)(cbase + (c < cq ? c : 0)) * 8);
+    if constexpr (MAXK > 0) braw[it] = V8<T>::load_raw(beta + (size_t)(cbase + (c < cq ? c : 0)) * 8);
   }
   const int row0 = blockIdx.x * rpb;
   for (int b0 = 0; b0 < rpb; b0 += kLnBatch) {
@@ -185,11 +259,30 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
           const int c = lane + it * 64;
           if (c < cq) {
             xraw[r][it] = V8<T>::load_raw(x + (size_t)row * d + (size_t)(cbase + c) * 8);
-            dyraw[r][it] = V8<T>::load_raw(dy + (size_t)row * d + (size_t)(cbase + c) * 8);
             float xv[8], dv[8], g[8];
             V8<T>::unpack(xraw[r][it], xv);
-            V8<T>::unpack(dyraw[r][it], dv);
             V8<T>::unpack(graw[it], g);
+            if constexpr (MAXK > 0) {
+              float b[8], dz[8];
+              V8<T>::unpack(braw[it], b);
+              load_small<T, 8 / MAXK>(dy + (size_t)row * (d / MAXK) + (size_t)(cbase + c) * (8 / MAXK), dz);
+#pragma unroll
+              for (int w = 0; w < 8 / MAXK; ++w) {
+                int arg = 0;
+                float m = ln_affine_rounded<T>(xv[w * MAXK], mu[r], rs[r], g[w * MAXK], b[w * MAXK]);
+#pragma unroll
+                for (int i = 1; i < MAXK; ++i) {
+                  const float a = ln_affine_rounded<T>(xv[w * MAXK + i], mu[r], rs[r], g[w * MAXK + i], b[w * MAXK + i]);
+                  if (a > m) { m = a; arg = i; }      // strict: ties keep the first
+                }
+#pragma unroll
+                for (int i = 0; i < MAXK; ++i) dv[w * MAXK + i] = i == arg ? dz[w] : 0.0f;
+              }
+              dyraw[r][it] = V8<T>::make_raw(dv);     // exact: dz values and zeros are of type T
+            } else {
+              dyraw[r][it] = V8<T>::load_raw(dy + (size_t)row * d + (size_t)(cbase + c) * 8);
+              V8<T>::unpack(dyraw[r][it], dv);
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
               const float xh = (xv[i] - mu[r]) * rs[r];
@@ -325,13 +418,13 @@ __global__ __launch_bounds__(256) void reduce_rows_accum_kernel(const float* __r
   }
 }
 
-template <typename T, bool DEC>
+template <typename T, bool DEC, int MAXK = 0>
 swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows, int d,
                              float eps, const int8_t* codes, const float* scales, T* xdec, hipStream_t st) {
   const int grid = std::min((rows + kLnWaves - 1) / kLnWaves, 256 * 8);
-#define LN_FWD(NIT)                                                                                              \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, NIT, DEC>), dim3(grid), dim3(kLnThreads), 0, st, x, g, b, y, mean, rstd, \
-                     rows, d, eps, codes, scales, xdec)
+#define LN_FWD(NIT)                                                                                           \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, NIT, DEC, MAXK>), dim3(grid), dim3(kLnThreads), 0, st, x, g, b, y, mean, \
+                     rstd, rows, d, eps, codes, scales, xdec)
   if (d <= 512) LN_FWD(1);
   else if (d <= 1024) LN_FWD(2);
   else if (d <= 2048) LN_FWD(4);
@@ -342,15 +435,15 @@ swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* me
   return launch_status();
 }
 
-template <typename T, bool ENC>
+template <typename T, bool ENC, int MAXK = 0>
 swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const float* rstd, const T* g,
                              const T* dres, T* dx, float* partial, int rows, int d, int8_t* codes, float* scales,
-                             hipStream_t st) {
+                             hipStream_t st, const T* beta = nullptr) {
   const int rpb = ln_rows_per_block(rows);
   const int grid = (rows + rpb - 1) / rpb;
-#define LN_BWD(NITQ)                                                                                             \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ, ENC>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
-                     dres, dx, partial, rows, d, codes, scales, rpb)
+#define LN_BWD(NITQ)                                                                                                \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ, ENC, MAXK>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
+                     dres, dx, partial, rows, d, codes, scales, rpb, beta)
   if (d <= 2048) LN_BWD(1);
   else if (d <= 4096) LN_BWD(2);
   else if (d <= 8192) LN_BWD(4);
@@ -407,6 +500,54 @@ swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, con
   const int grid = (d + 63) / 64;
   hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3(grid, 2), dim3(256), 0, st, partial, P, d, (size_t)2 * d, dgamma,
                      dbeta);
+  return launch_status();
+}
+
+// Fused LayerNorm + maxout_k (k in {2, 4, 8}, d % 8 == 0; anything else: SWARM_ERR_SHAPE, nothing launched).
+// k = -1: mean and rstd only.
+swarm_status layernorm_fwd_maxout(const void* x, const void* gamma, const void* beta, void* z, float* mean, float* rstd,
+                                  int T, int d, int k, float eps, bool bf16, hipStream_t st) {
+#define LN_MO(TT, K)                                                                                               \
+  return ln_fwd_dispatch<TT, false, K>((const TT*)x, (const TT*)gamma, (const TT*)beta, (TT*)z, mean, rstd, T, d, eps, \
+                                       nullptr, nullptr, nullptr, st)
+  if (bf16) {
+    if (k == 2) LN_MO(bf16_raw, 2);
+    if (k == 4) LN_MO(bf16_raw, 4);
+    if (k == 8) LN_MO(bf16_raw, 8);
+    if (k == -1) LN_MO(bf16_raw, -1);
+  } else {
+    if (k == 2) LN_MO(float, 2);
+    if (k == 4) LN_MO(float, 4);
+    if (k == 8) LN_MO(float, 8);
+    if (k == -1) LN_MO(float, -1);
+  }
+#undef LN_MO
+  return SWARM_ERR_SHAPE;
+}
+
+// dx = LN-backward of the gradient that maxout_k routes from dz [T, d / k] to the first maximum of every window of
+// the normalised row (recomputed from x, mean, rstd); dgamma, dbeta += as in layernorm_bwd.
+swarm_status layernorm_bwd_maxout(const void* dz, const void* x, const float* mean, const float* rstd,
+                                  const void* gamma, const void* beta, void* dx, float* dgamma, float* dbeta,
+                                  float* partial, int T, int d, int k, bool bf16, hipStream_t st) {
+  swarm_status s = SWARM_ERR_SHAPE;
+#define LN_MOB(TT, K)                                                                                             \
+  s = ln_bwd_dispatch<TT, false, K>((const TT*)dz, (const TT*)x, mean, rstd, (const TT*)gamma, (const TT*)nullptr, \
+                                    (TT*)dx, partial, T, d, nullptr, nullptr, st, (const TT*)beta)
+  if (bf16) {
+    if (k == 2) LN_MOB(bf16_raw, 2);
+    else if (k == 4) LN_MOB(bf16_raw, 4);
+    else if (k == 8) LN_MOB(bf16_raw, 8);
+  } else {
+    if (k == 2) LN_MOB(float, 2);
+    else if (k == 4) LN_MOB(float, 4);
+    else if (k == 8) LN_MOB(float, 8);
+  }
+#undef LN_MOB
+  if (s != SWARM_OK) return s;
+  const int P = (T + ln_rows_per_block(T) - 1) / ln_rows_per_block(T);
+  hipLaunchKernelGGL(reduce_rows_accum_kernel, dim3((d + 63) / 64, 2), dim3(256), 0, st, partial, P, d, (size_t)2 * d,
+                     dgamma, dbeta);
   return launch_status();
 }
 

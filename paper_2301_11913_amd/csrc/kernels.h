@@ -66,6 +66,16 @@ size_t layernorm_bwd_scratch_floats(int T, int d);
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
                            bool bf16, hipStream_t st, int8_t* codes = nullptr, float* scales = nullptr);
+// LayerNorm fused with the maxout that follows it in the compression-aware sender (k in {2, 4, 8}; other k:
+// SWARM_ERR_SHAPE and nothing launched): z [T, d/k] = maxout_k(LN(x)), the normalised row is never stored.  The
+// window maximum is taken on the normalised values rounded to the dtype.  k = -1: mean and rstd only.
+swarm_status layernorm_fwd_maxout(const void* x, const void* gamma, const void* beta, void* z, float* mean, float* rstd,
+                                  int T, int d, int k, float eps, bool bf16, hipStream_t st);
+// Its backward: recomputes the normalised row from x, mean, rstd, routes dz [T, d/k] to the first maximum of every
+// window and applies the LayerNorm backward; dgamma, dbeta += as in layernorm_bwd.
+swarm_status layernorm_bwd_maxout(const void* dz, const void* x, const float* mean, const float* rstd,
+                                  const void* gamma, const void* beta, void* dx, float* dgamma, float* dbeta,
+                                  float* partial, int T, int d, int k, bool bf16, hipStream_t st);
 // LayerNorm of a row that arrives int8-encoded: xdec receives the decoded row (fused stage-entry decode).
 swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void* xdec, const void* gamma,
                                   const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
