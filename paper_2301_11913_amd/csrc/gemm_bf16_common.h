@@ -113,19 +113,37 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
     const int c4 = lane % LPR4, rsub4 = lane / LPR4;
     const int colf = col0 + 4 * c4;
     const bool colf_ok = !GUARD || colf < p.N;
+    // The gradient values a row group adds to are requested one group ahead: their latency is then paid once,
+    // not once per group.
+    constexpr int NPS4 = 32 / RPP4;
+    const bool accum = epi == EPI_ACCUM_F32;
+    float4 cn[NPS4];
+    auto load_c = [&](int i) __attribute__((always_inline)) {
+#pragma unroll
+      for (int ps = 0; ps < NPS4; ++ps) {
+        const int row = row0 + i * 32 + ps * RPP4 + rsub4;
+        if (accum && colf_ok && (!GUARD || row < p.M))
+          cn[ps] = *reinterpret_cast<const float4*>(c + (size_t)row * p.ldc + colf);
+      }
+    };
+    load_c(0);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       stage_rows32<FM, FN>(acc, i, stage, lane);
+      float4 cc[NPS4];
 #pragma unroll
-      for (int ps = 0; ps < 32 / RPP4; ++ps) {
+      for (int ps = 0; ps < NPS4; ++ps) cc[ps] = cn[ps];
+      if (i + 1 < FM) load_c(i + 1);
+#pragma unroll
+      for (int ps = 0; ps < NPS4; ++ps) {
         const int rl = ps * RPP4 + rsub4;
         const int row = row0 + i * 32 + rl;
         const float4 v = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 4 * c4);
         if (!colf_ok || (GUARD && row >= p.M)) continue;
         float4* dst = reinterpret_cast<float4*>(c + (size_t)row * p.ldc + colf);
         float4 o = v;
-        if (epi == EPI_ACCUM_F32) {
-          o = *dst;
+        if (accum) {
+          o = cc[ps];
           o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
         }
         *dst = o;
