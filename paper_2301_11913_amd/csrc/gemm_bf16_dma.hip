@@ -317,18 +317,21 @@ __device__ __forceinline__ bf16x8 frag_trans16(const bf16_raw* tile, int col_bas
   return __builtin_bit_cast(bf16x8, make_uint4(a.x, a.y, b.x, b.y));
 }
 
-// Which fragment of the NEXT sub-step is requested behind MFMA slot n (slot = 4 * row + column): 0 .. FM-1 = A row,
-// FM + j = B column j, -1 = none.  kind 0: a sub-step without barrier; kind 1: barrier behind slot 3, nothing of
-// the next slice may be read before it.
+// Which fragment of the NEXT sub-step is requested behind MFMA slot n (slot = FN * row + column): 0 .. FM-1 = A row,
+// FM + j = B column j, -1 = none.  kind 0: a sub-step without barrier; kind 1: barrier behind slot FN - 1, nothing
+// of the next slice may be read before it.  No slot holds two fragments: B sits in column 1 of a row (column 0
+// when a row has only two), A in the last column (A_0 of kind 1: the first one behind the barrier).
 template <int FM, int FN>
 constexpr int k32_read_at(int kind, int n) {
+  constexpr int BCOL = FN > 2 ? 1 : 0;
   if (n % FN == FN - 1 && n / FN >= 1) return n / FN;                      // A_i behind the last MFMA of row i >= 1
   if (kind == 0) {
     if (n == FN - 1) return 0;                                             // A_0 behind the last MFMA of row 0
-    if (n % FN == 1 && n / FN < FN) return FM + n / FN;                    // B_j behind slot FN * j + 1
+    if (n % FN == BCOL && n / FN < FN) return FM + n / FN;                 // B_j in row j
   } else {
+    constexpr int R0 = FN > 2 ? 1 : 2;                                     // first row with a B request
     if (n == FN) return 0;                                                 // A_0 behind the first MFMA after the barrier
-    if (n % FN == 1 && n / FN >= 1 && n / FN <= FN) return FM + n / FN - 1;  // B_j behind slot FN * (j + 1) + 1
+    if (n % FN == BCOL && n / FN >= R0 && n / FN < R0 + FN) return FM + n / FN - R0;   // B_j in row j + R0
   }
   return -1;
 }
@@ -362,7 +365,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
   constexpr int IPW = (BM + BN) * DBK / 512 / NW;       // load instructions per wavefront per stage
   constexpr int IPA = BM * DBK / 512 / NW;
   static_assert(DBK == 64 && NS == 2, "two 32-deep sub-steps per slice, two stages");
-  static_assert(FN >= 2 && FM >= FN + 1 && 2 * IPW + FN + 2 <= FM * FN, "read / load slots of a sub-step");
+  static_assert(FN >= 2 && FM >= FN + 2 && 2 * IPW + FN + 2 <= FM * FN, "read / load slots of a sub-step");
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
 
   int tile_m, tile_n;
@@ -645,6 +648,17 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   if (g.M % 256 == 0 && g.N % 256 == 0 && (long)(g.M / 256) * (g.N / 256) >= 160) {
     k.tiles_m = g.M / 256; k.tiles_n = g.N / 256;
     return launch_dma_layout<256, 256, 2, 4>(k, g.a_trans, g.b_trans, st);
+  }
+  // Too few 256 x 256 tiles, but 256 x 128 tiles make one nearly full round (a 2048-row microbatch times a
+  // 4096-wide weight: 256 tiles): one round of those beats two rounds of 128 x 128.  A wavefront's sub-tile is
+  // 32 columns wide there, so the epilogues that need 64 (fused encode, GeGLU) stay on the 128 x 128 tiles.
+  if (!g.a_trans && g.M % 256 == 0 && g.N % 128 == 0 && g.epilogue != EPI_BIAS_RESID_ENCODE &&
+      g.epilogue != EPI_BIAS_GEGLU) {
+    const long tiles = (long)(g.M / 256) * (g.N / 128);
+    if (tiles >= 192 && tiles <= 256) {
+      k.tiles_m = g.M / 256; k.tiles_n = g.N / 128;
+      return launch_dma_layout<256, 128, 2, 4>(k, g.a_trans, g.b_trans, st);
+    }
   }
   if (g.M % 128 == 0 && g.N % 128 == 0) {
     k.tiles_m = g.M / 128; k.tiles_n = g.N / 128;

@@ -153,6 +153,15 @@ def test_gemm_ragged_last_round(epi, b_t):
     gemm_case(2048, 12288, 256, False, b_t, epi, seed=40 + epi)
 
 
+@pytest.mark.parametrize("epi,b_t", [(0, False), (0, True), (1, False), (2, False), (3, False), (4, True)])
+@pytest.mark.parametrize("shape", [(2048, 4096, 64), (2048, 4096, 448), (1536, 4096, 256), (1792, 4224, 128)])
+def test_gemm_256x128_tiles(shape, epi, b_t):
+    """192 .. 256 tiles of 256 x 128 (a 2048-row microbatch times a 4096-wide weight): one round of those instead
+    of two rounds of 128 x 128.  One, two, four and seven 64-deep slices; a column count that is no multiple of 256."""
+    M, N, K = shape
+    gemm_case(M, N, K, False, b_t, epi, seed=60 + epi)
+
+
 def test_gemm_splitk_encode_equals_encode_of_stored():
     """EPI 6 (bias + residual, int8-encoded) through the split path: codes and scales are those of the stand-alone
     codec applied to what the bias + residual epilogue stores (same scratch, same summation order)."""
