@@ -23,6 +23,7 @@ struct KArgs {
   int split;       // EPI_DGEGLU, EPI_BIAS_GEGLU
   int tiles_m, tiles_n;
   int group_m;   // tile rows walked together (L2 reuse of the B panel)
+  int stream;    // != 0: the epilogue's global accesses are non-temporal (see store_stream)
   int ksplit;    // > 1: the grid holds ksplit workgroups per tile, each takes K / ksplit and stores its fp32 partial
   float* part;   //      tile sums to part + index * M * N (a second kernel adds them and applies the epilogue)
 };
@@ -67,6 +68,37 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// Streaming accesses of the epilogues: an output tile is written once and the residual / pre-activation / gradient
+// rows are read once, so they are marked non-temporal and do not push the operand panels out of the L2.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ void store_stream(void* dst, const uint4& v) {
+  const u32x4_t t = {v.x, v.y, v.z, v.w};
+  if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(dst));
+  else *reinterpret_cast<u32x4_t*>(dst) = t;
+}
+template <bool NT>
+__device__ __forceinline__ void store_stream(float* dst, const float4& v) {
+  const f32x4_t t = {v.x, v.y, v.z, v.w};
+  if constexpr (NT) __builtin_nontemporal_store(t, reinterpret_cast<f32x4_t*>(dst));
+  else *reinterpret_cast<f32x4_t*>(dst) = t;
+}
+template <bool NT>
+__device__ __forceinline__ uint4 load_stream(const bf16_raw* src) {
+  u32x4_t t;
+  if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src));
+  else t = *reinterpret_cast<const u32x4_t*>(src);
+  return make_uint4(t[0], t[1], t[2], t[3]);
+}
+template <bool NT>
+__device__ __forceinline__ float4 load_stream(const float* src) {
+  f32x4_t t;
+  if constexpr (NT) t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(src));
+  else t = *reinterpret_cast<const f32x4_t*>(src);
+  return make_float4(t[0], t[1], t[2], t[3]);
+}
+
 __device__ __forceinline__ uint4 pack8_bf16(const float (&x)[8]) {
   return make_uint4(cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3]), cvt_pk_bf16(x[4], x[5]), cvt_pk_bf16(x[6], x[7]));
 }
@@ -99,8 +131,8 @@ __device__ __forceinline__ void stage_rows32(const Acc16<FM, FN>& acc, int i, fl
       for (int r = 0; r < 4; ++r) stage[(16 * h + 4 * q + r) * kEpiPitch + 16 * j + l16] = acc.blk[2 * i + h][j][r];
 }
 
-template <int FM, int FN, bool GUARD, typename Acc>
-__device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, int row0, int col0, int l32,
+template <int FM, int FN, bool GUARD, bool NT, typename Acc>
+__device__ __forceinline__ void gemm_epilogue_nt(const KArgs& p, const Acc& acc, int row0, int col0, int l32,
                                               int lg, float* stage) {
   static_assert(32 * FN <= kEpiPitch - 4, "the LDS patch holds 64 columns");
   const int epi = p.epilogue;
@@ -123,7 +155,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
       for (int ps = 0; ps < NPS4; ++ps) {
         const int row = row0 + i * 32 + ps * RPP4 + rsub4;
         if (accum && colf_ok && (!GUARD || row < p.M))
-          cn[ps] = *reinterpret_cast<const float4*>(c + (size_t)row * p.ldc + colf);
+          cn[ps] = load_stream<NT>(c + (size_t)row * p.ldc + colf);
       }
     };
     load_c(0);
@@ -140,13 +172,12 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
         const int row = row0 + i * 32 + rl;
         const float4 v = *reinterpret_cast<const float4*>(stage + rl * kEpiPitch + 4 * c4);
         if (!colf_ok || (GUARD && row >= p.M)) continue;
-        float4* dst = reinterpret_cast<float4*>(c + (size_t)row * p.ldc + colf);
         float4 o = v;
         if (accum) {
           o = cc[ps];
           o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
         }
-        *dst = o;
+        store_stream<NT>(c + (size_t)row * p.ldc + colf, o);
       }
     }
     return;
@@ -175,12 +206,12 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
 #pragma unroll
         for (int e = 0; e < 8; ++e) { g[e] += bg[e]; u[e] += bu[e]; }
         if (p.C2) {
-          *reinterpret_cast<uint4*>(p.C2 + row * p.ldc2 + feat) = pack8_bf16(g);
-          *reinterpret_cast<uint4*>(p.C2 + row * p.ldc2 + p.split + feat) = pack8_bf16(u);
+          store_stream<NT>(p.C2 + row * p.ldc2 + feat, pack8_bf16(g));
+          store_stream<NT>(p.C2 + row * p.ldc2 + p.split + feat, pack8_bf16(u));
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) g[e] = gelu_fast(g[e]) * u[e];
-        *reinterpret_cast<uint4*>(G + row * p.ldc + feat) = pack8_bf16(g);
+        store_stream<NT>(G + row * p.ldc + feat, pack8_bf16(g));
       }
     }
     return;
@@ -212,7 +243,7 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
         // stage-exit codec fused: the 8 lanes of a row segment hold one 64-element block.  Values are
         // rounded to bf16 first, so codes and scales equal the stand-alone encode of the stored tensor.
         float a[8];
-        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+        unpack8(load_stream<NT>(p.aux + (size_t)row * p.ldaux + col), a);
         float amax = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -241,18 +272,18 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
         for (int e = 0; e < 8; ++e) x[e] += bias[e];
       } else if (epi == EPI_BIAS_RESID) {
         float a[8];
-        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+        unpack8(load_stream<NT>(p.aux + (size_t)row * p.ldaux + col), a);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = x[e] + bias[e] + a[e];
       } else if (epi == EPI_BIAS_GELU) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] += bias[e];
-        if (p.C2) *reinterpret_cast<uint4*>(p.C2 + (size_t)row * p.ldc2 + col) = pack8_bf16(x);
+        if (p.C2) store_stream<NT>(p.C2 + (size_t)row * p.ldc2 + col, pack8_bf16(x));
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = gelu_fast(x[e]);
       } else if (epi == EPI_DGELU) {
         float a[8];
-        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), a);
+        unpack8(load_stream<NT>(p.aux + (size_t)row * p.ldaux + col), a);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] *= gelu_grad_fast(a[e]);
       } else if (epi == EPI_BIAS_ROPE) {
@@ -272,18 +303,26 @@ __device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, in
         }
       } else if (epi == EPI_DGEGLU) {
         float gt[8], up[8], o2[8];
-        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + col), gt);
-        unpack8(*reinterpret_cast<const uint4*>(p.aux + (size_t)row * p.ldaux + p.split + col), up);
+        unpack8(load_stream<NT>(p.aux + (size_t)row * p.ldaux + col), gt);
+        unpack8(load_stream<NT>(p.aux + (size_t)row * p.ldaux + p.split + col), up);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           o2[e] = x[e] * gelu_fast(gt[e]);
           x[e] = x[e] * up[e] * gelu_grad_fast(gt[e]);
         }
-        *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + p.split + col) = pack8_bf16(o2);
+        store_stream<NT>(C + (size_t)row * p.ldc + p.split + col, pack8_bf16(o2));
       }
-      *reinterpret_cast<uint4*>(C + (size_t)row * p.ldc + col) = pack8_bf16(x);
+      store_stream<NT>(C + (size_t)row * p.ldc + col, pack8_bf16(x));
     }
   }
+}
+
+// NT (p.stream): the epilogue's global accesses are non-temporal; two copies of the code, one uniform branch.
+template <int FM, int FN, bool GUARD, typename Acc>
+__device__ __forceinline__ void gemm_epilogue(const KArgs& p, const Acc& acc, int row0, int col0, int l32,
+                                              int lg, float* stage) {
+  if (p.stream) gemm_epilogue_nt<FM, FN, GUARD, true>(p, acc, row0, col0, l32, lg, stage);
+  else gemm_epilogue_nt<FM, FN, GUARD, false>(p, acc, row0, col0, l32, lg, stage);
 }
 
 }  // namespace

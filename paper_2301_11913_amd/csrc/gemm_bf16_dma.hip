@@ -16,7 +16,6 @@
 //
 // One workgroup owns one output tile and walks K in order: deterministic.
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -595,6 +594,9 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
   k.ksplit = 1; k.part = nullptr;
+  // An output of at least twice the 32 MB of L2 cannot wait there for its consumer; written (and its residual /
+  // pre-activation / gradient rows read) non-temporally it leaves the operand panels in the L2 instead.
+  k.stream = (size_t)g.M * g.N * (g.epilogue == EPI_ACCUM_F32 ? 4 : 2) >= ((size_t)64 << 20);
   // Few output tiles, long K, no transposed A (forward and dgrad products of short microbatches): the 256 x 256
   // tiles at ksplit workgroups per tile fill the chip where 128 x 128 tiles would run at their lower rate.
   // Every part keeps at least 4096 of K, which is where the second kernel's pass over the partial sums pays.

@@ -162,6 +162,13 @@ def test_gemm_256x128_tiles(shape, epi, b_t):
     gemm_case(M, N, K, False, b_t, epi, seed=60 + epi)
 
 
+@pytest.mark.parametrize("epi,b_t", [(0, False), (0, True), (1, False), (2, False), (3, False), (4, True)])
+def test_gemm_streaming_outputs(epi, b_t):
+    """Outputs of 64 MB and more are written, and their residual / pre-activation rows read, with non-temporal
+    accesses (another copy of the epilogue code): 8192 x 4096 in bf16 is 64 MB."""
+    gemm_case(8192, 4096, 128, False, b_t, epi, seed=70 + epi)
+
+
 def test_gemm_splitk_encode_equals_encode_of_stored():
     """EPI 6 (bias + residual, int8-encoded) through the split path: codes and scales are those of the stand-alone
     codec applied to what the bias + residual epilogue stores (same scratch, same summation order)."""
