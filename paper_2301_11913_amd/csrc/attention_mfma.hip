@@ -662,21 +662,11 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
   }   // pass
 }
 
-template <typename Kern>
-swarm_status set_lds(Kern kern, size_t bytes, bool& done) {
-  if (!done) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
-      return SWARM_ERR_LAUNCH;
-    done = true;
-  }
-  return SWARM_OK;
-}
-
 template <int DH>
 swarm_status launch_fwd(const bf16_raw* qkv, bf16_raw* o, float* lse, int B, int S, int H, hipStream_t st) {
   constexpr size_t lds_bytes = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
-  static bool a0 = false;
-  if (set_lds(attn_fwd_kernel<DH>, lds_bytes, a0) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  static LdsOptIn a0;
+  if (lds_opt_in((const void*)attn_fwd_kernel<DH>, lds_bytes, a0) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(attn_fwd_kernel<DH>, dim3((((S + 127) / 128 + 1) / 2) * H * B), dim3(kThreads), lds_bytes, st,
                      qkv, o, lse, S, H);
   return launch_status();
@@ -687,9 +677,9 @@ swarm_status launch_bwd(const bf16_raw* qkv, const bf16_raw* o, const bf16_raw* 
                         bf16_raw* dqkv, int B, int S, int H, hipStream_t st) {
   constexpr size_t lds_dkdv = (size_t)2 * (2 * 64 * DH + 256) * sizeof(bf16_raw);
   constexpr size_t lds_dq = (size_t)2 * 2 * 64 * DH * sizeof(bf16_raw);
-  static bool a1 = false, a2 = false;
-  if (set_lds(attn_bwd_dkdv_kernel<DH>, lds_dkdv, a1) != SWARM_OK) return SWARM_ERR_LAUNCH;
-  if (set_lds(attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  static LdsOptIn a1, a2;
+  if (lds_opt_in((const void*)attn_bwd_dkdv_kernel<DH>, lds_dkdv, a1) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  if (lds_opt_in((const void*)attn_bwd_dq_kernel<DH>, lds_dq, a2) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(attn_delta_kernel<DH>, dim3(B * S), dim3(kThreads), 0, st, o, dout, delta, S, H);
   dim3 grid((((S + 127) / 128 + 1) / 2) * H * B);   // workgroups take pairs of tiles
   hipLaunchKernelGGL(attn_bwd_dkdv_kernel<DH>, grid, dim3(kDkDvThreads), lds_dkdv, st, qkv, dout, lse, delta, dqkv, S,

@@ -51,4 +51,21 @@ inline swarm_status launch_status() {
   return hipGetLastError() == hipSuccess ? SWARM_OK : SWARM_ERR_LAUNCH;
 }
 
+// A kernel that wants more than 64 KB of dynamic LDS has to be told so once per device.  `done` is the caller's
+// static record (one per kernel instantiation), indexed by device.
+constexpr int kMaxDevices = 64;
+struct LdsOptIn {
+  bool done[kMaxDevices] = {};
+};
+inline swarm_status lds_opt_in(const void* kernel, size_t bytes, LdsOptIn& rec) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SWARM_ERR_LAUNCH;
+  if (!rec.done[dev]) {
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+      return SWARM_ERR_LAUNCH;
+    rec.done[dev] = true;
+  }
+  return SWARM_OK;
+}
+
 }  // namespace swarm

@@ -189,13 +189,8 @@ template <int BM, int BN, int WM, int WN, bool A_T, bool B_T, bool GUARD>
 swarm_status launch(const KArgs& k, hipStream_t st) {
   constexpr size_t lds_bytes = (size_t)2 * (BM + BN) * BK * sizeof(bf16_raw);
   auto kern = gemm_bf16_kernel<BM, BN, WM, WN, A_T, B_T, GUARD>;
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
-        hipSuccess)
-      return SWARM_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsOptIn opted;   // per instantiation
+  if (lds_opt_in((const void*)kern, lds_bytes, opted) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n), dim3(WM * WN * 64), lds_bytes, st, k);
   return launch_status();
 }

@@ -488,13 +488,8 @@ swarm_status launch_dma(const KArgs& k, hipStream_t st) {
   void (*kern)(KArgs);
   if constexpr (SWARM_GEMM_K32 && BM == 256) kern = gemm_bf16_k32_kernel<BM, BN, WM, WN, A_T, B_T>;
   else kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, A_T, B_T>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
-        hipSuccess)
-      return SWARM_ERR_LAUNCH;
-    attr_set = true;
-  }
+  static LdsOptIn opted;   // per instantiation
+  if (lds_opt_in((const void*)kern, lds_bytes, opted) != SWARM_OK) return SWARM_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n * (k.ksplit > 1 ? k.ksplit : 1)), dim3(WM * WN * 64), lds_bytes,
                      st, k);
   return launch_status();
