@@ -23,7 +23,10 @@
  *   - results are bitwise reproducible from call to call (no float atomics); which
  *     kernels run depends on the shapes, so the same rows inside a microbatch of
  *     another size agree to the rounding of the dtype, not bit for bit;
- *   - all matrices are row-major with the last index contiguous.
+ *   - all matrices are row-major with the last index contiguous;
+ *   - a call only enqueues kernels and device-to-device copies, so it may be captured into a HIP graph and
+ *     replayed, once one call with the same shapes has run outside a capture on that device (the first launch of
+ *     a kernel on a device sets its LDS size, which a capture does not record).
  */
 #ifndef SWARM_STAGE_H
 #define SWARM_STAGE_H

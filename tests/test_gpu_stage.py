@@ -63,6 +63,47 @@ def test_accumulation_and_determinism():
     assert np.array_equal(one["grad_in"], again["grad_in"])
 
 
+def test_forward_and_backward_replay_from_a_hip_graph():
+    """The entry points only enqueue kernels and one device-to-device copy on the given stream (no allocation, no
+    memset, no synchronisation), so a captured forward + backward replays: three replays, each after eager work
+    that dirties the outputs, give bitwise the eager results; grad_params grow by one contribution per replay."""
+    import paper_2301_11913_amd as sw
+    from stage_util import to_dev
+    wl = synth.WORKLOADS["stage2_bf16_d1024"].replace(seq=128, batch=2)
+    params, x, G = synth.make_params(wl), synth.make_x_in(wl), synth.make_grad_out(wl)
+    cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
+                         wl.ln_eps, wl.block)
+    dp = [{k: to_dev(p[k], wl) for k in sw.PARAM_FIELDS} for p in params]
+    xd, Gd = to_dev(x, wl), to_dev(G, wl)
+    ws_f = torch.empty(sw.swarm_stage_workspace_bytes(cfg, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(sw.swarm_stage_workspace_bytes(cfg, True), dtype=torch.uint8, device="cuda")
+    new_grads = lambda: [{k: torch.zeros(p[k].shape, dtype=torch.float32, device="cuda") for k in sw.PARAM_FIELDS}
+                         for p in params]
+    # eager reference (also the warm-up that opts the kernels into their LDS sizes before the capture)
+    y0, gin0, gp0 = torch.empty_like(xd), torch.empty_like(xd), new_grads()
+    sw.swarm_stage_forward(cfg, dp, xd, y0, ws_f)
+    sw.swarm_stage_backward(cfg, dp, xd, Gd, gin0, gp0, ws_b)
+    torch.cuda.synchronize()
+    y, gin, gp = torch.empty_like(xd), torch.empty_like(xd), new_grads()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sw.swarm_stage_forward(cfg, dp, xd, y, ws_f)
+        sw.swarm_stage_backward(cfg, dp, xd, Gd, gin, gp, ws_b)
+    for g in gp:                      # whatever the capture itself did to the accumulators is discarded
+        for t in g.values():
+            t.zero_()
+    for n in range(1, 4):
+        y.fill_(3.0); gin.fill_(3.0); ws_f.fill_(0xA5); ws_b.fill_(0x5A)   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y0) and torch.equal(gin, gin0), n
+        for g, g0 in zip(gp, gp0):
+            for k in g:
+                one = g0[k].double()
+                assert torch.allclose(g[k].double(), n * one, rtol=1e-6, atol=1e-6 * float(one.abs().max())), (n, k)
+
+
 def test_shared_equals_unrolled_on_gpu():
     wl = synth.Workload(name="shared", dtype="bf16", d_model=256, n_heads=2, d_ffn=512, seq=96, batch=2,
                         n_layers=1, n_repeat=3, grad_sigma=1e-2, seed=77)
