@@ -16,7 +16,6 @@
 // walked in groups of rows to keep the B panel resident.
 //
 // Deterministic: one workgroup owns an output tile and walks K in order.
-#include <cstdlib>
 #include <vector>
 
 #include "gemm_bf16_common.h"
@@ -244,10 +243,9 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   if (g.epilogue == EPI_BIAS_ROPE && (!g.rope || g.rope_S < 1 || g.rope_dh % 8 || g.rope_cols % 8)) return SWARM_ERR_SHAPE;
   if (g.epilogue == EPI_DGEGLU && (g.split != g.N || !g.aux)) return SWARM_ERR_SHAPE;
   if (!vec_ok || (g.a_trans && !g.b_trans)) return gemm_generic(g, true, st);
-  static const bool use_dma = std::getenv("SWARM_GEMM_NO_DMA") == nullptr;
   if (g.epilogue == EPI_BIAS_GEGLU)   // needs the gathered B tile of the direct-to-LDS kernel
-    return use_dma ? gemm_bf16_dma(g, st) : SWARM_ERR_SHAPE;
-  if (use_dma) {
+    return gemm_bf16_dma(g, st);
+  {
     const swarm_status s = gemm_bf16_dma(g, st);   // tile-aligned shapes: pipelined direct-to-LDS kernel
     if (s != SWARM_ERR_SHAPE) return s;
   }

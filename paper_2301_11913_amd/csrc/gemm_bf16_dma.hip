@@ -179,10 +179,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   // and 1 are requested up front, slice kt+2 behind the barrier that ends slice kt); otherwise one sub-step
   // later, at the top of the next iteration.  Measured: EARLY gains 1-3 % on the 256 x 256 tile and loses 5 % on
   // the 128 x 128 one (two workgroups per compute unit already overlap each other's loads).
-#ifndef SWARM_GEMM_EARLY
-#define SWARM_GEMM_EARLY (BM == 256)
-#endif
-  constexpr bool EARLY = SWARM_GEMM_EARLY;
+  constexpr bool EARLY = BM == 256;
   issue(0, 0);
   if constexpr (EARLY) {
     issue(min(1, KT - 1), 1);
@@ -481,12 +478,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
 swarm_status launch_dma(const KArgs& k, hipStream_t st) {
   constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * DBK * sizeof(bf16_raw);
-#ifndef SWARM_GEMM_K32
-#define SWARM_GEMM_K32 1
-#endif
-  // 256 x 256 tiles: the 16 x 16 x 32 kernel; the 128 x 128 tile stays on 32 x 32 x 16 (measured 2 % faster there)
+  // 256-row tiles: the 16 x 16 x 32 kernel; the 128 x 128 tile stays on 32 x 32 x 16 (measured 2 % faster there)
   void (*kern)(KArgs);
-  if constexpr (SWARM_GEMM_K32 && BM == 256) kern = gemm_bf16_k32_kernel<BM, BN, WM, WN, A_T, B_T>;
+  if constexpr (BM == 256) kern = gemm_bf16_k32_kernel<BM, BN, WM, WN, A_T, B_T>;
   else kern = gemm_bf16_dma_kernel<BM, BN, WM, WN, A_T, B_T>;
   static LdsOptIn opted;   // per instantiation
   if (lds_opt_in((const void*)kern, lds_bytes, opted) != SWARM_OK) return SWARM_ERR_LAUNCH;
