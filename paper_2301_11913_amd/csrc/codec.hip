@@ -61,8 +61,8 @@ template <> struct ScaleIO<uint16_t> {
   static __device__ __forceinline__ float load(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
 };
 
-__device__ __forceinline__ int quantise(float x, float scale) {
-  float q = rintf(x / scale);
+__device__ __forceinline__ int quantise(float x, const BlockDivisor& scale) {
+  float q = rintf(scale.quotient(x));
   q = fminf(fmaxf(q, -127.0f), 127.0f);
   return (int)q;
 }
@@ -97,8 +97,9 @@ __global__ __launch_bounds__(kThreads) void codec_encode_kernel(const T* __restr
 #pragma unroll
       for (int i = 0; i < 8; ++i) c[i] = 0;
     } else {
+      const BlockDivisor div(scale);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) c[i] = quantise(x[i], scale);
+      for (int i = 0; i < 8; ++i) c[i] = quantise(x[i], div);
     }
     if (base + kPerLane <= n_elems) {
       uint2 out;

@@ -47,6 +47,31 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// x / s, correctly rounded, for many x and one s (the block scale of the boundary codec, whose codes are
+// rint(x / s) and have to come out bit for bit).  The correctly rounded fp32 division is the sequence
+//   r0 = rcp(s); r = fma(fma(-s, r0, 1), r0, r0); q = x r; q = fma(fma(-s, q, x), r, q); q = fma(fma(-s, q, x), r, q)
+// wrapped in operand scaling and a fix-up that only act when an exponent is extreme.  With s in [2^-100, 2^100]
+// they act only on numerators below 2^-103 or quotients in the subnormal range: there |x / s| < 1/8, and whatever
+// the unscaled sequence returns for it also rounds to the code 0.  So r is computed once per block and every
+// element costs one multiplication and four fused multiply-adds; any other s takes the plain division.
+struct BlockDivisor {
+  float s, r;
+  bool plain;
+  __device__ __forceinline__ explicit BlockDivisor(float scale) : s(scale) {
+    const uint32_t biased = (__float_as_uint(scale) >> 23) & 0xFFu;
+    plain = biased - 27u > 200u;
+    const float r0 = __builtin_amdgcn_rcpf(scale);
+    r = __builtin_fmaf(__builtin_fmaf(-scale, r0, 1.0f), r0, r0);
+  }
+  // a value whose rintf() equals rintf(x / s)
+  __device__ __forceinline__ float quotient(float x) const {
+    if (plain) return x / s;
+    float q = x * r;
+    q = __builtin_fmaf(__builtin_fmaf(-s, q, x), r, q);
+    return __builtin_fmaf(__builtin_fmaf(-s, q, x), r, q);
+  }
+};
+
 inline swarm_status launch_status() {
   return hipGetLastError() == hipSuccess ? SWARM_OK : SWARM_ERR_LAUNCH;
 }

@@ -328,9 +328,10 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
             const float sc = amax / 127.0f;
             uint32_t w[2] = {0u, 0u};
             if (sc != 0.0f) {
+              const BlockDivisor div(sc);
 #pragma unroll
               for (int i = 0; i < 8; ++i) {
-                const float q = fminf(fmaxf(rintf(o[i] / sc), -127.0f), 127.0f);
+                const float q = fminf(fmaxf(rintf(div.quotient(o[i])), -127.0f), 127.0f);
                 w[i >> 2] |= ((uint32_t)(int)q & 0xFFu) << (8 * (i & 3));
               }
             }

@@ -543,9 +543,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(KArgs p) {
     const float sc = amax / 127.0f;
     uint32_t w[2] = {0u, 0u};
     if (sc != 0.0f) {
+      const BlockDivisor div(sc);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const float q = fminf(fmaxf(rintf(x[e] / sc), -127.0f), 127.0f);
+        const float q = fminf(fmaxf(rintf(div.quotient(x[e])), -127.0f), 127.0f);
         w[e >> 2] |= ((uint32_t)(int)q & 0xFFu) << (8 * (e & 3));
       }
     }
