@@ -37,3 +37,24 @@ extern "C" int swarm_kernel_attention_bwd(int dtype, const void* qkv, const void
                                           void* stream) {
   return attention_bwd(qkv, o, dout, lse, delta, dqkv, B, S, H, dh, dtype != 0, (hipStream_t)stream);
 }
+
+// codes[i] = clamp(rint(x[i] / scale[i]), -127, 127) through BlockDivisor, the shared-reciprocal form of the
+// correctly rounded division that the codec kernels use (scale[i] > 0, finite).
+namespace {
+__global__ __launch_bounds__(256) void quantise_pairs_kernel(const float* __restrict__ x,
+                                                             const float* __restrict__ scale, size_t n,
+                                                             int8_t* __restrict__ codes) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const BlockDivisor div(scale[i]);
+  codes[i] = (int8_t)(int)fminf(fmaxf(rintf(div.quotient(x[i])), -127.0f), 127.0f);
+}
+}  // namespace
+extern "C" int swarm_kernel_quantise_pairs(const float* x, const float* scale, size_t n, int8_t* codes,
+                                           void* stream) {
+  if (n == 0) return SWARM_OK;
+  if (!x || !scale || !codes) return SWARM_ERR_NULL;
+  hipLaunchKernelGGL(quantise_pairs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, x,
+                     scale, n, codes);
+  return launch_status();
+}

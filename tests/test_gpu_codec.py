@@ -149,3 +149,49 @@ def test_codec_s16_all_bf16_patterns():
         gc, gs = _encode_gpu_s16(x, True)
         assert np.array_equal(rs, gs) and np.array_equal(rc, gc)
         assert np.array_equal(ocodec.decode(rc, rs, out="bf16"), _decode_gpu_s16(rc, rs, x.size, True))
+
+
+def test_shared_reciprocal_division_gives_the_codes_of_the_ieee_division():
+    """The kernels divide by a block's scale through one reciprocal per block and fused multiply-adds per element
+    (the correctly rounded division's own sequence with its scale-dependent half hoisted).  Against numpy's fp32
+    division, for scales of every exponent, absmax / 127 of bf16 maxima and their bf16 roundings, both edges of
+    the range that takes the hoisted form; x = every bf16 value the scale admits (|x| <= 127.5 scale), and fp32
+    values within 4 ulps of every tie (k + 1/2) scale."""
+    import ctypes
+    import paper_2301_11913_amd as sw
+    lib = sw.load_library()
+    lib.swarm_kernel_quantise_pairs.restype = ctypes.c_int
+    lib.swarm_kernel_quantise_pairs.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                                ctypes.c_void_p]
+    rng = np.random.default_rng(5)
+    sc = [rng.integers(1, 0x7F800000, 600, dtype=np.uint32).view(np.float32)]              # any positive fp32
+    amax = (rng.integers(1, 0x7F80, 400, dtype=np.uint32) << 16).astype(np.uint32).view(np.float32)
+    s = amax / np.float32(127.0)
+    sc += [s, ocodec.bf16_bits_to_f32(ocodec.f32_to_bf16_bits(s))]
+    edges = np.concatenate([np.arange(20, 34), np.arange(220, 235)]).astype(np.uint32)       # biased exponents
+    sc.append(((edges[:, None] << 23) | rng.integers(0, 1 << 23, (len(edges), 8), dtype=np.uint32)).reshape(-1)
+              .astype(np.uint32).view(np.float32))
+    sc = np.concatenate(sc).astype(np.float32)
+    sc = sc[np.isfinite(sc) & (sc > 0)]
+    bf = (np.arange(65536, dtype=np.uint32) << 16).view(np.float32)
+    bf = bf[np.isfinite(bf)]
+    k = np.arange(-127, 128, dtype=np.float32) + np.float32(0.5)
+    total = 0
+    for chunk in np.array_split(sc, 16):
+        with np.errstate(over="ignore", invalid="ignore"):
+            ties = (k[None, :] * chunk[:, None]).astype(np.float32)                           # [S, 255]
+            near = (ties.view(np.uint32)[:, :, None] + np.arange(-4, 5, dtype=np.int64)[None, None, :]).astype(np.uint32)
+            near = near.view(np.float32).reshape(len(chunk), -1)
+            x = np.concatenate([np.broadcast_to(bf, (len(chunk), len(bf))), near, -near], axis=1)
+            s2 = np.broadcast_to(chunk[:, None], x.shape)
+            keep = np.isfinite(x) & (np.abs(x) <= np.float32(127.5) * s2)
+            x, s2 = np.ascontiguousarray(x[keep]), np.ascontiguousarray(s2[keep])
+            want = np.clip(np.rint(x / s2), -127, 127).astype(np.int8)
+        xd, sd = torch.from_numpy(x).cuda(), torch.from_numpy(s2).cuda()
+        got = torch.full((x.size,), 99, dtype=torch.int8, device="cuda")
+        assert lib.swarm_kernel_quantise_pairs(xd.data_ptr(), sd.data_ptr(), x.size, got.data_ptr(), None) == 0
+        torch.cuda.synchronize()
+        bad = np.nonzero(got.cpu().numpy() != want)[0]
+        assert bad.size == 0, (x[bad[:4]], s2[bad[:4]], want[bad[:4]])
+        total += x.size
+    assert total > 2e7
