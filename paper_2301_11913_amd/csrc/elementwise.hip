@@ -34,6 +34,10 @@ template <> struct V8<bf16_raw> {
       x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
     }
   }
+  // the compiler may not carry anything computed from r across this point (keeps the unpacked copy out of registers)
+  static __device__ __forceinline__ void opaque(Raw& r) {
+    asm volatile("" : "+v"(r.v.x), "+v"(r.v.y), "+v"(r.v.z), "+v"(r.v.w));
+  }
   static __device__ __forceinline__ void load(const bf16_raw* p, float (&x)[8]) {
     uint4 v = *reinterpret_cast<const uint4*>(p);
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -62,6 +66,7 @@ template <> struct V8<float> {
   static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
     x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w; x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
   }
+  static __device__ __forceinline__ void opaque(Raw&) {}      // fp32: the raw form is the unpacked form
   static __device__ __forceinline__ void load(const float* p, float (&x)[8]) {
     float4 a = *reinterpret_cast<const float4*>(p);
     float4 b = *reinterpret_cast<const float4*>(p + 4);
@@ -129,9 +134,12 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
   const int wave = threadIdx.x >> 6;
   const int nchunk = d >> 3;
   const float inv_d = 1.0f / (float)d;
+  // The row stays in registers as loaded (Raw: 4 registers per 8 bf16 values) and is unpacked once per pass —
+  // a third of the registers of an unpacked copy, which is what lets enough wavefronts reside to cover the loads.
+  typedef typename V8<T>::Raw Raw;
   for (int row = blockIdx.x * kLnWaves + wave; row < rows; row += gridDim.x * kLnWaves) {
     const T* xr = x + (size_t)row * d;
-    float v[NIT][8];
+    Raw raw[NIT];
     float s = 0.f;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -146,38 +154,50 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
 #pragma unroll
           for (int i = 0; i < 8; ++i) t[i] = (float)(int)(int8_t)((w[i >> 2] >> (8 * (i & 3))) & 0xFF) * sc;
           V8<T>::store(xdec + e0, t);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) v[it][i] = V8<T>::rounded(t[i]);   // the values just stored
+          raw[it] = V8<T>::make_raw(t);                                  // the values just stored
         } else {
-          V8<T>::load(xr + c * 8, v[it]);
+          raw[it] = V8<T>::load_raw(xr + c * 8);
         }
+      }
+    }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s += v[it][i];
+    for (int it = 0; it < NIT; ++it) {
+      if (lane + it * 64 < nchunk) {
+        float v[8];
+        V8<T>::unpack(raw[it], v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += v[i];
       }
     }
     const float mu = wave_sum(s) * inv_d;
     float q = 0.f;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int c = lane + it * 64;
-      if (c < nchunk) {
+    for (int it = 0; it < NIT; ++it) V8<T>::opaque(raw[it]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { const float t = v[it][i] - mu; q += t * t; }
+    for (int it = 0; it < NIT; ++it) {
+      if (lane + it * 64 < nchunk) {
+        float v[8];
+        V8<T>::unpack(raw[it], v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const float t = v[i] - mu; q += t * t; }
       }
     }
     const float var = wave_sum(q) * inv_d;
     const float r = 1.0f / sqrtf(var + eps);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) V8<T>::opaque(raw[it]);
     if constexpr (MAXK == 0) {
       T* yr = y + (size_t)row * d;
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
         const int c = lane + it * 64;
         if (c < nchunk) {
-          float g[8], b[8], o[8];
+          float v[8], g[8], b[8], o[8];
+          V8<T>::unpack(raw[it], v);
           V8<T>::load(gamma + c * 8, g);
           V8<T>::load(beta + c * 8, b);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) o[i] = (v[it][i] - mu) * r * g[i] + b[i];
+          for (int i = 0; i < 8; ++i) o[i] = (v[i] - mu) * r * g[i] + b[i];
           V8<T>::store(yr + c * 8, o);
         }
       }
@@ -187,15 +207,16 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
       for (int it = 0; it < NIT; ++it) {
         const int c = lane + it * 64;
         if (c < nchunk) {
-          float g[8], b[8], o[8];
+          float v[8], g[8], b[8], o[8];
+          V8<T>::unpack(raw[it], v);
           V8<T>::load(gamma + c * 8, g);
           V8<T>::load(beta + c * 8, b);
 #pragma unroll
           for (int w = 0; w < 8 / MAXK; ++w) {
-            float m = ln_affine_rounded<T>(v[it][w * MAXK], mu, r, g[w * MAXK], b[w * MAXK]);
+            float m = ln_affine_rounded<T>(v[w * MAXK], mu, r, g[w * MAXK], b[w * MAXK]);
 #pragma unroll
             for (int i = 1; i < MAXK; ++i)
-              m = fmaxf(m, ln_affine_rounded<T>(v[it][w * MAXK + i], mu, r, g[w * MAXK + i], b[w * MAXK + i]));
+              m = fmaxf(m, ln_affine_rounded<T>(v[w * MAXK + i], mu, r, g[w * MAXK + i], b[w * MAXK + i]));
             o[w] = m;
           }
           store_small<T, 8 / MAXK>(zr + c * (8 / MAXK), o);
