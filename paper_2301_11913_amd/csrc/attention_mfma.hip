@@ -630,12 +630,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_bwd_dq_kernel(const bf16_raw
         auto frag2 = [&](int n) { return T::cols_raw(sK, 32 * (n % DB), 32 * kb2 + 16 * (n / DB), lane); };
 #pragma unroll
         for (int n = 0; n < PF; ++n) kt[n] = frag2(n);
+        if (diag) {   // only a tile on the diagonal (or past the sequence end) has keys to mask
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -L2));
-          const int kv = kv0 + 32 * kb2 + 8 * (r >> 2) + 4 * lg + (r & 3);
-          if (diag && kv > qrow) p = 0.f;
-          dp[r] = p * (dp[r] - dl);
+          for (int r = 0; r < 16; ++r) {
+            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -L2));
+            const int kv = kv0 + 32 * kb2 + 8 * (r >> 2) + 4 * lg + (r & 3);
+            if (kv > qrow) p = 0.f;
+            dp[r] = p * (dp[r] - dl);
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dp[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, -L2)) * (dp[r] - dl);
         }
         bf16x8 dsf[2];
 #pragma unroll
