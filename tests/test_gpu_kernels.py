@@ -226,7 +226,8 @@ def _attn_ref(qkv, dout, B, S, H, dh):
 
 
 @pytest.mark.parametrize("shape", [(2, 128, 2, 64), (1, 512, 3, 128), (3, 37, 2, 128), (2, 200, 1, 64),
-                                   (1, 1, 2, 64), (1, 1000, 2, 128), (2, 2048, 2, 128)])
+                                   (1, 1, 2, 64), (1, 1000, 2, 128), (2, 2048, 2, 128),
+                                   (1, 4100, 1, 128), (1, 2500, 2, 64), (5, 129, 3, 128), (1, 191, 1, 64)])
 def test_attention_bf16(shape):
     B, S, H, dh = shape
     lib = _attn_lib()
