@@ -498,60 +498,42 @@ __global__ __launch_bounds__(kDkDvThreads) void attn_bwd_dkdv_kernel(const bf16_
         for (int n = 0; n < PF; ++n) ct[n] = frag2(n);
         // (the row statistics below are ordinary LDS loads issued AFTER those transpose reads: LDS returns in
         // order, so whatever count the compiler waits for before using them only over-waits)
-        // d_head = 64 has the registers for one element loop per role (the dV wavefronts then load no delta and
-        // compute no dS) with the mask as one unsigned comparison: -13 % on the kernel.  At d_head = 128 the kernel
-        // sits at 256 registers and that form spills (+6 %), so it keeps the shared loop.
-        if constexpr (DH == 64) {
+        {
           // p = 0 for queries before this lane's key (diagonal tiles only) and past the sequence end: one unsigned
-          // comparison of q - lo against S - lo, with lo = the lane's key on a diagonal tile and 0 elsewhere
+          // comparison of q - lo against S - lo, with lo = the lane's key on a diagonal tile and 0 elsewhere.
+          // The row statistics are read four queries at a time, right where they are used (few live registers).
           const int lo = diag ? kvrow : 0;
-          const uint32_t span = (uint32_t)(S - lo);            // kvrow < S + 31 always; lanes with kvrow >= S own no row
+          const uint32_t span = (uint32_t)(S - lo);
           const int qrel = q0 + 32 * qb + 4 * lg - lo;
           if (is_dk) {
-            float Ls[16], Ds[16];
-  #pragma unroll
+#pragma unroll
             for (int g = 0; g < 4; ++g) {
               const int rbase = 32 * qb + 8 * g + 4 * lg;
               const float4 L = *reinterpret_cast<const float4*>(sstat + rbase);
               const float4 D = *reinterpret_cast<const float4*>(sstat + 64 + rbase);
-              Ls[4 * g] = L.x; Ls[4 * g + 1] = L.y; Ls[4 * g + 2] = L.z; Ls[4 * g + 3] = L.w;
-              Ds[4 * g] = D.x; Ds[4 * g + 1] = D.y; Ds[4 * g + 2] = D.z; Ds[4 * g + 3] = D.w;
-            }
-  #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[r] * kLog2e));
-              if ((uint32_t)(qrel + 8 * (r >> 2) + (r & 3)) >= span) p = 0.f;
-              s[r] = p * (dp[r] - Ds[r]);                        // dS
+              const float Lg[4] = {L.x, L.y, L.z, L.w}, Dg[4] = {D.x, D.y, D.z, D.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int r = 4 * g + e;
+                float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Lg[e] * kLog2e));
+                if ((uint32_t)(qrel + 8 * g + e) >= span) p = 0.f;
+                s[r] = p * (dp[r] - Dg[e]);                        // dS
+              }
+              if constexpr (DH == 128) __builtin_amdgcn_sched_barrier(0);
             }
           } else {
-            float Ls[16];
-  #pragma unroll
+#pragma unroll
             for (int g = 0; g < 4; ++g) {
               const float4 L = *reinterpret_cast<const float4*>(sstat + 32 * qb + 8 * g + 4 * lg);
-              Ls[4 * g] = L.x; Ls[4 * g + 1] = L.y; Ls[4 * g + 2] = L.z; Ls[4 * g + 3] = L.w;
+              const float Lg[4] = {L.x, L.y, L.z, L.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int r = 4 * g + e;
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Lg[e] * kLog2e));
+                s[r] = (uint32_t)(qrel + 8 * g + e) >= span ? 0.f : p;   // P
+              }
+              if constexpr (DH == 128) __builtin_amdgcn_sched_barrier(0);
             }
-  #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[r] * kLog2e));
-              s[r] = (uint32_t)(qrel + 8 * (r >> 2) + (r & 3)) >= span ? 0.f : p;   // P
-            }
-          }
-        } else {
-          float Ls[16], Ds[16];
-  #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int rbase = 32 * qb + 8 * g + 4 * lg;
-            const float4 L = *reinterpret_cast<const float4*>(sstat + rbase);
-            const float4 D = *reinterpret_cast<const float4*>(sstat + 64 + rbase);
-            Ls[4 * g] = L.x; Ls[4 * g + 1] = L.y; Ls[4 * g + 2] = L.z; Ls[4 * g + 3] = L.w;
-            Ds[4 * g] = D.x; Ds[4 * g + 1] = D.y; Ds[4 * g + 2] = D.z; Ds[4 * g + 3] = D.w;
-          }
-  #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -Ls[r] * kLog2e));
-            const int q = q0 + 32 * qb + 8 * (r >> 2) + 4 * lg + (r & 3);
-            if ((diag && kvrow > q) || q >= S) p = 0.f;
-            s[r] = is_dk ? p * (dp[r] - Ds[r]) : p;      // dS for the dK wavefront, P for the dV wavefront
           }
         }
         bf16x8 bf[2];
