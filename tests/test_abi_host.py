@@ -150,3 +150,51 @@ def test_codec_s16_validation_without_gpu(lib):
     assert enc(None, 1, C.c_size_t(64), 64, dummy, dummy, None) == -1
     assert enc(dummy, 1, C.c_size_t(64), 64, dummy, C.c_void_p(257), None) == -2     # scales 2-byte aligned
     assert lib.swarm_codec_decode_s16(dummy, None, C.c_size_t(64), 64, dummy, 1, None) == -1
+
+
+def test_headers_are_c99_and_binding_structs_match_their_layout(tmp_path):
+    """The ABI headers compile as plain C99 (and as C++), and every struct the binding mirrors with ctypes has the
+    size and field offsets the C compiler gives it."""
+    import ctypes
+    import shutil
+    import subprocess
+    from paper_2301_11913_amd import binding as b
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(ROOT, "include")
+    structs = {
+        "swarm_stage_config": (b._Config, "swarm_stage.h"),
+        "swarm_block_params": (b._BlockPtrs, "swarm_stage.h"),
+        "swarm_block_grads": (b._BlockPtrs, "swarm_stage.h"),
+        "swarm_boundary_config": (b._BoundaryConfig, "swarm_boundary.h"),
+        "swarm_compress_params": (b._Ptrs3, "swarm_boundary.h"),
+        "swarm_decompress_grads": (b._Ptrs3, "swarm_boundary.h"),
+        "swarm_head_config": (b._HeadConfig, "swarm_head.h"),
+        "swarm_head_params": (b._Ptrs3, "swarm_head.h"),
+        "swarm_lamb_config": (b._LambConfig, "swarm_optim.h"),
+    }
+    c_fields = {"swarm_compress_params": ["ln_g", "ln_b", "w_c"], "swarm_decompress_grads": ["ln_g", "ln_b", "w_d"],
+                "swarm_head_params": ["ln_g", "ln_b", "w_vocab"]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>']
+    lines += ['#include "%s"' % h for h in sorted({h for _, h in structs.values()})]
+    lines.append("int main(void) {")
+    for name, (ct, _) in structs.items():
+        names = c_fields.get(name, [f for f, _ in ct._fields_])
+        lines.append('  printf("%s %%zu", sizeof(%s));' % (name, name))
+        for f in names:
+            lines.append('  printf(" %%zu", offsetof(%s, %s));' % (name, f))
+        lines.append('  printf("\\n");')
+    lines.append("  return 0; }")
+    src = tmp_path / "probe.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = {l.split()[0]: [int(x) for x in l.split()[1:]] for l in out if l.strip()}
+    for name, (ct, _) in structs.items():
+        want = [ctypes.sizeof(ct)] + [getattr(ct, f).offset for f, _ in ct._fields_]
+        assert seen[name] == want, (name, seen[name], want)
+    if shutil.which("g++"):
+        cxx = tmp_path / "probe.cpp"
+        cxx.write_text("\n".join('#include "%s"' % h for h in sorted(os.listdir(inc)) if h.endswith(".h")) + "\nint main() { return 0; }\n")
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cxx)], check=True)
