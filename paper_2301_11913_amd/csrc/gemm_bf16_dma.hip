@@ -35,6 +35,12 @@ constexpr int KCH = DBK / 8;   // 16-byte chunks per row of a non-transposed til
 __device__ __forceinline__ int swz_rows(int row) {
   return DBK == 64 ? ((row & 7) ^ ((row >> 3) & 1)) : ((row >> 2) & 3);
 }
+// The same for the fragments of the 16 x 16 x 32 kernel, whose lanes read 16 rows x 4 k-quarters: measured with a
+// read-only loop, the swizzle above gives that lane order 151 B/clk per compute unit (two-way conflicts) and this
+// one 277 B/clk, the rate of a linear read.
+__device__ __forceinline__ int swz_rows16(int row) { return row & 7; }
+template <bool K32>
+__device__ __forceinline__ int swz_rows_of(int row) { return K32 ? swz_rows16(row) : swz_rows(row); }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression
 template <typename F, int... I>
@@ -61,7 +67,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // glu_split != 0 (GeGLU forward, B = W1 [2*split, K]): the tile's rows are gathered so that every 64-row group
 // (one wavefront column) holds 32 gate rows followed by the 32 up rows of the same features; r0 then counts
 // features: tile row 64*w + c -> W1 row r0 + 32*w + (c & 31) + (c >= 32 ? split : 0).
-template <int BR, int NW, bool TRANS>
+template <int BR, int NW, bool TRANS, bool K32 = false>
 __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
                                                int wave, int lane, int t, int glu_split = 0) {
   {
@@ -69,7 +75,7 @@ __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, i
     const bf16_raw* src;
     if constexpr (!TRANS) {
       const int row = q * (64 / KCH) + lane / KCH;
-      const int chunk = (lane % KCH) ^ swz_rows(row);
+      const int chunk = (lane % KCH) ^ swz_rows_of<K32>(row);
       const int grow = glu_split ? r0 + 32 * (row >> 6) + (row & 31) + ((row & 32) ? glu_split : 0) : r0 + row;
       src = g + (size_t)grow * ld + k0 + chunk * 8;
     } else {
@@ -82,13 +88,13 @@ __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, i
   }
 }
 
-template <int BR, int NW, bool TRANS>
+template <int BR, int NW, bool TRANS, bool K32 = false>
 __device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
                                            int wave, int lane, int glu_split = 0) {
   constexpr int NINST = BR * DBK / 512;
   static_assert(NINST % NW == 0, "tile rows must split evenly over the wavefronts");
 #pragma unroll
-  for (int t = 0; t < NINST / NW; ++t) issue_tile_one<BR, NW, TRANS>(g, ld, r0, k0, lds, wave, lane, t, glu_split);
+  for (int t = 0; t < NINST / NW; ++t) issue_tile_one<BR, NW, TRANS, K32>(g, ld, r0, k0, lds, wave, lane, t, glu_split);
 }
 
 // Fragment (32 GEMM rows x 16 k) for v_mfma_f32_32x32x16_bf16 from a non-transposed tile.
@@ -293,7 +299,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
 // 16 rows x 32 k fragment of a non-transposed tile (rows of DBK k)
 __device__ __forceinline__ bf16x8 frag_rows16(const bf16_raw* tile, int row_base, int kk, int l16, int q) {
   const int row = row_base + l16;
-  const int chunk = (4 * kk + q) ^ swz_rows(l16);
+  const int chunk = (4 * kk + q) ^ swz_rows16(l16);
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + row * DBK + chunk * 8));
 }
 // the same fragment from a [k][BR] tile through the LDS transpose read (two plain instructions, caller waits)
@@ -396,12 +402,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
       for (int r = 0; r < 4; ++r) acc.blk[i][j][r] = 0.f;
 
   const int KT = p.K / DBK;
-  issue_tile<BM, NW, A_T>(p.A, p.lda, m0, 0, lds, wave, lane);
-  issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, 0, lds + BM * DBK, wave, lane, glu);
+  issue_tile<BM, NW, A_T, true>(p.A, p.lda, m0, 0, lds, wave, lane);
+  issue_tile<BN, NW, B_T, true>(p.B, p.ldb, n0, 0, lds + BM * DBK, wave, lane, glu);
   {
     const int k1 = min(1, KT - 1) * DBK;
-    issue_tile<BM, NW, A_T>(p.A, p.lda, m0, k1, lds + STAGE, wave, lane);
-    issue_tile<BN, NW, B_T>(p.B, p.ldb, n0, k1, lds + STAGE + BM * DBK, wave, lane, glu);
+    issue_tile<BM, NW, A_T, true>(p.A, p.lda, m0, k1, lds + STAGE, wave, lane);
+    issue_tile<BN, NW, B_T, true>(p.B, p.ldb, n0, k1, lds + STAGE + BM * DBK, wave, lane, glu);
   }
   wait_vmcnt<IPW>();
   __builtin_amdgcn_s_barrier();
@@ -452,8 +458,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
       if constexpr (f >= FM) nb[f - FM] = read_b(nA, f - FM, nkk);
       if constexpr (KIND == 1 && n >= FN + 2 && (n - FN) % 2 == 0 && (n - FN - 2) / 2 < IPW) {
         constexpr int t = (n - FN - 2) / 2;
-        if constexpr (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
-        else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+        if constexpr (t < IPA) issue_tile_one<BM, NW, A_T, true>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+        else issue_tile_one<BN, NW, B_T, true>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
       }
       __builtin_amdgcn_sched_barrier(0);
     });

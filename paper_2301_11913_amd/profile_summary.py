@@ -4,6 +4,12 @@
     python -m paper_2301_11913_amd.profile_summary pmc    <fetch>_counter_collection.csv <write>_counter_collection.csv
                                                           [kernel name prefix = gemm_bf16 [largest]]
 
+    python -m paper_2301_11913_amd.profile_summary counters <counter_collection.csv> [more .csv ...]
+
+`counters` prints, per kernel family (GEMM: per instantiation; others: name up to the template arguments), the sum over all launches of every
+counter found in the given rocprofv3 --pmc runs of bench.py, and each counter as a fraction of SQ_BUSY_CU_CYCLES
+(per-CU busy cycles) resp. of SQ_WAVE_CYCLES where those are present in the same file.
+
 `pmc` expects two runs of `bench.py --copy-calibration` under `rocprofv3 --pmc FETCH_SIZE` and
 `--pmc WRITE_SIZE`.  The counters are scaled by what they read for the plain 1 GiB device copies of
 that run (each reads 2^30 and writes 2^30 bytes), then averaged over the launches of the kernels whose name starts
@@ -70,5 +76,36 @@ def pmc(fetch_csv: str, write_csv: str, prefix: str = "gemm_bf16", which: str = 
     print(json.dumps(out, indent=1))
 
 
+def counters(*paths: str) -> None:
+    def fam(n):   # GEMM kernels per instantiation (tile and operand layouts), the others per name
+        n = _short(n)
+        return n if n.startswith("gemm_bf16") else n.split("<")[0]
+    for path in paths:
+        acc = collections.defaultdict(lambda: collections.defaultdict(float))
+        launches = collections.defaultdict(set)
+        for r in csv.DictReader(open(path)):
+            k = fam(r["Kernel_Name"])
+            if not (k.startswith("gemm_bf16") or k.startswith("attn_")):
+                continue
+            acc[k][r["Counter_Name"]] += float(r["Counter_Value"])
+            launches[k].add(r["Dispatch_Id"])
+        names = sorted({c for v in acc.values() for c in v})
+        print("| kernel family | launches | " + " | ".join("`%s`" % c for c in names) + " |")
+        print("|---|---|" + "---|" * len(names))
+        for k in sorted(acc):
+            v = acc[k]
+            cells = []
+            for c in names:
+                cell = "%.4g" % v[c]
+                for base in ("SQ_BUSY_CU_CYCLES", "SQ_WAVE_CYCLES"):
+                    if base in v and c != base and v[base] > 0 and not c.startswith("SQ_INSTS") and c != "SQ_WAVES" \
+                            and not (base == "SQ_WAVE_CYCLES" and "SQ_BUSY_CU_CYCLES" in v and not c.startswith("SQ_WAIT")):
+                        cell += " (%.1f %% of %s)" % (100.0 * v[c] / v[base], base.replace("SQ_", "").lower())
+                        break
+                cells.append(cell)
+            print("| `%s` | %d | " % (k, len(launches[k])) + " | ".join(cells) + " |")
+        print()
+
+
 if __name__ == "__main__":
-    {"stats": stats, "pmc": pmc}[sys.argv[1]](*sys.argv[2:])
+    {"stats": stats, "pmc": pmc, "counters": counters}[sys.argv[1]](*sys.argv[2:])
