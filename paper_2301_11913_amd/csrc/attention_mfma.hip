@@ -267,6 +267,10 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
       // S^T = K Q^T: NQK MFMAs, fragment n = (ks = n / 2, key block n % 2); the read of fragment n+PF sits behind
       // MFMA n, so reads run PF multiplies ahead of their use
       constexpr int NQK = 2 * KS, PF = 4, RING = 8;
+      // The score MFMAs run at raised wavefront priority, the softmax and the P V MFMAs at the normal one: the two
+      // wavefronts of a SIMD (from different workgroups) then fall out of step instead of both wanting the matrix
+      // pipe, then both the vector unit (-5 % on this kernel at B = 4, S = 2048; the backward kernels do not react).
+      __builtin_amdgcn_s_setprio(2);
       f32x16 s[2];
       zero(s);
       bf16x8 kr[RING];
@@ -283,6 +287,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(const bf16_raw* _
       }
       // O^T += V^T P^T: NPV MFMAs, fragment n = (dh block n % DB, key group n / DB); the first PF fragments of
       // V^T are requested now and arrive under the softmax arithmetic
+      __builtin_amdgcn_s_setprio(0);
       constexpr int NPV = 4 * DB;
       bf16x8 vr[RING];
 #pragma unroll
