@@ -268,7 +268,7 @@ LAMB_WORKLOADS = {
 
 def make_lamb_tensor(wl: LambWorkload, index: int, n: int = None):
     """(w, grad) fp32 of tensor `index` (flattened, optionally only the first n elements' worth): weights
-    N(0, 0.02) (vectors: around 1), gradients N(0, 1e-3) as after averaging over a large batch."""
+    N(0, 0.02) (vectors: about 1), gradients N(0, 1e-3) as after averaging over a large batch."""
     shape = wl.shapes[index]
     n = int(np.prod(shape)) if n is None else n
     w = normal(wl.seed, "lamb.w%d" % index, (n,), 1.0 if len(shape) == 1 else 0.0, 0.02, False)
