@@ -41,6 +41,19 @@ swarm_status swarm_lamb_step(const swarm_lamb_config *cfg, size_t n_elems, float
                              const float *grad, float *m, float *v, float *trust_ratio, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
 
+/* swarm_lamb_step for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same three kernels with their scratch (update
+ * direction, partial sums of the norms, ratio) in a static device array inside the library, 64 MiB + 33 KiB per GPU,
+ * held from the library's load until the process ends.  n_elems <= SWARM_LAMB_STATIC_MAX_ELEMS (one 4096 x 4096
+ * matrix), SWARM_ERR_WORKSPACE beyond; everything else as swarm_lamb_step, and the results are bit-identical to it.
+ * The call allocates and frees nothing.  All calls on one GPU share that GPU's array: calls that may overlap there
+ * (different streams, different threads) race; calls on one stream are ordered and safe.  Nothing has to be
+ * cleared between calls: every scratch word a call reads has been written by that call first. */
+#define SWARM_LAMB_STATIC_MAX_ELEMS ((size_t)1 << 24)
+swarm_status swarm_lamb_step_static(const swarm_lamb_config *cfg, size_t n_elems, float *master, void *param,
+                                    int32_t dtype, const float *grad, float *m, float *v, float *trust_ratio,
+                                    void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,6 +15,6 @@ from .binding import (  # noqa: F401
     swarm_decompress_forward, swarm_decompress_backward,
     HeadConfig, swarm_embedding_forward, swarm_embedding_backward, swarm_head_workspace_bytes,
     swarm_head_loss, swarm_head_loss_backward,
-    swarm_lamb_workspace_bytes, swarm_lamb_step,
+    swarm_lamb_workspace_bytes, swarm_lamb_step, swarm_lamb_step_static, SWARM_LAMB_STATIC_MAX_ELEMS,
     swarm_codec_encode_s16, swarm_codec_decode_s16,
 )

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm
                     "swarm_decompress_forward", "swarm_decompress_backward",
                     "swarm_embedding_forward", "swarm_embedding_backward", "swarm_head_workspace_bytes",
                     "swarm_head_loss", "swarm_head_loss_backward",
-                    "swarm_lamb_workspace_bytes", "swarm_lamb_step",
+                    "swarm_lamb_workspace_bytes", "swarm_lamb_step", "swarm_lamb_step_static",
                     "swarm_codec_encode_s16", "swarm_codec_decode_s16")
 SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
@@ -178,6 +178,9 @@ def load_library():
     lib.swarm_lamb_step.restype = C.c_int
     lib.swarm_lamb_step.argtypes = [C.POINTER(_LambConfig), C.c_size_t, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.swarm_lamb_step_static.restype = C.c_int
+    lib.swarm_lamb_step_static.argtypes = [C.POINTER(_LambConfig), C.c_size_t, C.c_void_p, C.c_void_p, C.c_int32,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
     _lib = lib
@@ -437,3 +440,21 @@ def swarm_lamb_step(master: torch.Tensor, param: Optional[torch.Tensor], grad: t
                                         workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
         raise SwarmError(st, "swarm_lamb_step")
+
+
+SWARM_LAMB_STATIC_MAX_ELEMS = 1 << 24
+
+
+def swarm_lamb_step_static(master: torch.Tensor, param: Optional[torch.Tensor], grad: torch.Tensor, m: torch.Tensor,
+                           v: torch.Tensor, step: int, lr: float = 1e-3, beta1: float = 0.9, beta2: float = 0.95,
+                           eps: float = 1e-6, weight_decay: float = 0.01, grad_scale: float = 1.0,
+                           trust_ratio: Optional[torch.Tensor] = None, stream=None) -> None:
+    for t in (master, grad, m, v):
+        if t.dtype != torch.float32:
+            raise TypeError("master weights, gradient and moments must be fp32")
+    cfg = _LambConfig(lr, beta1, beta2, eps, weight_decay, grad_scale, step)
+    st = load_library().swarm_lamb_step_static(C.byref(cfg), master.numel(), _ptr(master), _ptr(param),
+                                               _dtype_code(param) if param is not None else SWARM_F32, _ptr(grad),
+                                               _ptr(m), _ptr(v), _ptr(trust_ratio), _stream(stream))
+    if st != 0:
+        raise SwarmError(st, "swarm_lamb_step_static")

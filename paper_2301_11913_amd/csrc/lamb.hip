@@ -1,6 +1,7 @@
 // LAMB step for one parameter tensor (appendix "Additional Details for Section 4.3").  Three streaming kernels:
 // moments + update direction + per-workgroup partial sums of |w|^2 and |u|^2; a single-workgroup, fixed-order
 // reduction to the trust ratio; the weight update (and the copy in the stage's dtype).
+#include <atomic>
 #include <cmath>
 
 #include "kernels.h"
@@ -144,6 +145,13 @@ size_t n_blocks(size_t n) { return (n + kPerBlock - 1) / kPerBlock; }
 
 using namespace swarm;
 
+// Scratch of swarm_lamb_step_static: the update direction of the largest tensor it accepts, the partial sums of
+// its norms and the ratio.  One copy per GPU, at an address of its own, held until the process ends.
+constexpr size_t kStaticU = SWARM_LAMB_STATIC_MAX_ELEMS * sizeof(float);
+constexpr size_t kStaticPartial = (SWARM_LAMB_STATIC_MAX_ELEMS / kPerBlock) * 2 * sizeof(float);
+static_assert(SWARM_LAMB_STATIC_MAX_ELEMS % kPerBlock == 0 && kStaticU % 256 == 0 && kStaticPartial % 256 == 0, "");
+static __device__ __align__(256) unsigned char scratch[kStaticU + kStaticPartial + 256];
+
 extern "C" size_t swarm_lamb_workspace_bytes(size_t n_elems) {
   if (n_elems < 1) return 0;
   const size_t u = (n_elems * 4 + 255) & ~(size_t)255;
@@ -151,22 +159,15 @@ extern "C" size_t swarm_lamb_workspace_bytes(size_t n_elems) {
   return u + p + 256;
 }
 
-extern "C" swarm_status swarm_lamb_step(const swarm_lamb_config* cfg, size_t n, float* master, void* param,
-                                        int32_t dtype, const float* grad, float* m, float* v, float* trust_ratio,
-                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!cfg || !master || !grad || !m || !v || !workspace) return SWARM_ERR_NULL;
-  if (param && dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
-  if (n < 1 || cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) ||
-      !(cfg->eps > 0.f) || !(cfg->lr >= 0.f) || !(cfg->weight_decay >= 0.f))
-    return SWARM_ERR_SHAPE;
-  auto al16 = [](const void* q) { return ((uintptr_t)q & 15) == 0; };
-  if (!al16(master) || !al16(grad) || !al16(m) || !al16(v) || !al16(param) || ((uintptr_t)workspace & 255)) return SWARM_ERR_SHAPE;
-  if (swarm_lamb_workspace_bytes(n) > workspace_bytes) return SWARM_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)hip_stream;
-  float* u = (float*)workspace;
-  float* partial = (float*)((char*)workspace + ((n * 4 + 255) & ~(size_t)255));
+namespace swarm {
+namespace {
+
+// The three launches of one update; u [n] fp32, partial [2 * n_blocks(n)] fp32 and ratio [1] fp32 are scratch that
+// the kernels overwrite before they read it (nothing has to be cleared between calls).
+swarm_status lamb_launch(const swarm_lamb_config* cfg, size_t n, float* master, void* param, int32_t dtype,
+                         const float* grad, float* m, float* v, float* trust_ratio, float* u, float* partial,
+                         float* ratio, hipStream_t st) {
   const size_t nb = n_blocks(n);
-  float* ratio = partial + 2 * nb + (64 - (2 * nb) % 64) % 64;   // behind the partial sums, inside the slack
   Hyper h;
   h.beta1 = cfg->beta1; h.beta2 = cfg->beta2; h.one_m_beta1 = 1.0f - cfg->beta1; h.one_m_beta2 = 1.0f - cfg->beta2;
   h.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, (double)cfg->step)));
@@ -182,4 +183,62 @@ extern "C" swarm_status swarm_lamb_step(const swarm_lamb_config* cfg, size_t n, 
     hipLaunchKernelGGL(lamb_apply_kernel<float>, dim3(grid), dim3(kThreads), 0, st, master, u, (float*)param, ratio, n,
                        cfg->lr);
   return launch_status();
+}
+
+swarm_status lamb_check(const swarm_lamb_config* cfg, size_t n, const float* master, const void* param, int32_t dtype,
+                        const float* grad, const float* m, const float* v) {
+  if (!cfg || !master || !grad || !m || !v) return SWARM_ERR_NULL;
+  if (param && dtype != SWARM_F32 && dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
+  if (n < 1 || cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) || !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f) ||
+      !(cfg->eps > 0.f) || !(cfg->lr >= 0.f) || !(cfg->weight_decay >= 0.f))
+    return SWARM_ERR_SHAPE;
+  auto al16 = [](const void* q) { return ((uintptr_t)q & 15) == 0; };
+  if (!al16(master) || !al16(grad) || !al16(m) || !al16(v) || !al16(param)) return SWARM_ERR_SHAPE;
+  return SWARM_OK;
+}
+
+// Device address of `scratch` on the current device (looked up once per device; the array's name is only a
+// host-side handle and is never passed to a kernel).
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];
+unsigned char* static_scratch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return nullptr;
+    p = (unsigned char*)q;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  return p;
+}
+
+}  // namespace
+}  // namespace swarm
+
+extern "C" swarm_status swarm_lamb_step(const swarm_lamb_config* cfg, size_t n, float* master, void* param,
+                                        int32_t dtype, const float* grad, float* m, float* v, float* trust_ratio,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace) return SWARM_ERR_NULL;
+  const swarm_status chk = lamb_check(cfg, n, master, param, dtype, grad, m, v);
+  if (chk != SWARM_OK) return chk;
+  if ((uintptr_t)workspace & 255) return SWARM_ERR_SHAPE;
+  if (swarm_lamb_workspace_bytes(n) > workspace_bytes) return SWARM_ERR_WORKSPACE;
+  float* u = (float*)workspace;
+  float* partial = (float*)((char*)workspace + ((n * 4 + 255) & ~(size_t)255));
+  const size_t nb = n_blocks(n);
+  float* ratio = partial + 2 * nb + (64 - (2 * nb) % 64) % 64;   // behind the partial sums, inside the slack
+  return lamb_launch(cfg, n, master, param, dtype, grad, m, v, trust_ratio, u, partial, ratio, (hipStream_t)hip_stream);
+}
+
+extern "C" swarm_status swarm_lamb_step_static(const swarm_lamb_config* cfg, size_t n, float* master, void* param,
+                                               int32_t dtype, const float* grad, float* m, float* v,
+                                               float* trust_ratio, void* hip_stream) {
+  const swarm_status chk = lamb_check(cfg, n, master, param, dtype, grad, m, v);
+  if (chk != SWARM_OK) return chk;
+  if (n > SWARM_LAMB_STATIC_MAX_ELEMS) return SWARM_ERR_WORKSPACE;
+  unsigned char* base = static_scratch();
+  if (!base) return SWARM_ERR_LAUNCH;
+  return lamb_launch(cfg, n, master, param, dtype, grad, m, v, trust_ratio, (float*)base, (float*)(base + kStaticU),
+                     (float*)(base + kStaticU + kStaticPartial), (hipStream_t)hip_stream);
 }
