@@ -1,10 +1,10 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
 times (same shapes, same kernels).  bf16 tolerance 2e-2 max-normalised, codec bit-exact.
 
-The 8192-token end-to-end configuration is too large for the oracle as a whole, so there the oracle
-computes one sequence of the microbatch (sequences do not interact in x_out / grad_in), and the parameter
-gradients are checked (a) against the oracle for that sequence alone and (b) through the accumulation
-property: the full-microbatch gradients equal the sum of the per-sequence ones.
+The 8192-token end-to-end configuration goes through the oracle one sequence at a time (sequences do not
+interact in x_out / grad_in; the parameter gradients of the microbatch are the sum of the per-sequence ones).
+The fused-codec entry points, which are what bench.py times there, are compared bit for bit with
+decode -> stage -> encode at the same size.
 """
 import numpy as np
 import pytest
@@ -39,6 +39,7 @@ def test_shared4_stage():
     assert not bad, bad
 
 
+@pytest.mark.timeout(1200)
 def test_end_to_end_stage_with_codec():
     import paper_2301_11913_amd as sw
     wl = synth.WORKLOADS["e2e_bf16_d4096"]
@@ -58,15 +59,34 @@ def test_end_to_end_stage_with_codec():
     del xd, gd
 
     full = run_gpu(wl, params, x, G)
-    # (1) one sequence against the oracle: x_out, grad_in and that sequence's parameter gradients
+    # (1) every sequence against the oracle: x_out and grad_in row by row, and the full-microbatch parameter
+    # gradients against the sum of the oracle's per-sequence gradients (the oracle's accumulation property is
+    # pinned on the CPU: gradients of a microbatch are the sum over its sequences)
     one = wl.replace(batch=1)
-    ref0 = run_oracle(one, params, x[:1], G[:1], dt=np.float32)
+    ref_sum, ref0 = None, None
+    for b in range(wl.batch):
+        ref = run_oracle(one, params, x[b:b + 1], G[b:b + 1], dt=np.float32)
+        ex = max_norm_err(full["x_out"][b:b + 1], ref["x_out"])
+        eg = max_norm_err(full["grad_in"][b:b + 1], ref["grad_in"])
+        print("sequence %d: x_out %.2e grad_in %.2e" % (b, ex, eg), flush=True)
+        assert ex <= TOL and eg <= TOL, (b, ex, eg)
+        if ref_sum is None:
+            ref0 = ref
+            ref_sum = [{k: v.astype(np.float64) for k, v in g.items()} for g in ref["grads"]]
+        else:
+            for l in range(wl.n_layers):
+                for k in ref_sum[l]:
+                    ref_sum[l][k] += ref["grads"][l][k]
+    for l in range(wl.n_layers):
+        for k in ref_sum[l]:
+            e = max_norm_err(full["grads"][l][k], ref_sum[l][k])
+            assert e <= TOL, ("full-microbatch gradient", l, k, e)
+    # the single-sequence GPU run (other kernels: some products are cut along K at 2048 rows) meets the oracle too
     gpu0 = run_gpu(one, params, x[:1], G[:1])
     errs, bad = compare(gpu0, ref0, TOL)
-    print("sequence 0", {k: "%.2e" % v for k, v in errs.items()})
+    print("sequence 0 alone", {k: "%.2e" % v for k, v in errs.items()})
     assert not bad, bad
-    assert max_norm_err(full["x_out"][:1], ref0["x_out"]) <= TOL
-    assert max_norm_err(full["grad_in"][:1], ref0["grad_in"]) <= TOL
+    del ref_sum, ref0
     # sequences are independent: the full run reproduces the single-sequence run up to the summation order of the
     # products that the library cuts along K at 2048 rows and does not cut at 8192 (fp32 partial sums, so a few bf16
     # roundings differ by one unit after two blocks; one bf16 unit of the largest element is 2^-7 of it)
@@ -94,3 +114,41 @@ def test_end_to_end_stage_with_codec():
         torch.cuda.synchronize()
         rc, rs = ocodec.encode(full[key].astype(np.float32).reshape(-1))
         assert np.array_equal(rc, codes.cpu().numpy()) and np.array_equal(rs, scales.cpu().numpy())
+
+
+@pytest.mark.timeout(600)
+def test_end_to_end_fused_codec_equals_separate_calls():
+    """What bench.py times at this size: swarm_stage_forward_coded / swarm_stage_backward_coded on 8192 x 4096 (the
+    256 x 256 GEMM tile with the int8-encoding epilogue and its non-temporal copy, LayerNorm forward decoding and
+    LayerNorm backward encoding at 16 rows per workgroup).  Codes, scales, the decoded input and every parameter
+    gradient must equal, bit for bit, those of swarm_codec_decode -> swarm_stage_forward / backward ->
+    swarm_codec_encode, which the test above ties to the oracle."""
+    from test_gpu_coded import _run
+    _run(synth.WORKLOADS["e2e_bf16_d4096"])
+
+
+def test_gemm_encoding_epilogue_large_tiles():
+    """The int8-encoding epilogue on 256 x 256 tiles (512 of them) with a 64 MB bf16 equivalent output, i.e. its
+    non-temporal form: codes and scales equal the stand-alone codec applied to what the bias + residual epilogue
+    stores, and that stored tensor meets the fp64 definition."""
+    import ctypes as C
+    import paper_2301_11913_amd as sw
+    from test_gpu_kernels import _splitk_call, _lib, _bf
+    M, N, K = 8192, 4096, 256
+    lib = _lib()
+    A = _bf(synth.normal(5, "A", (M, K))); B = _bf(synth.normal(5, "B", (N, K)))
+    bias = _bf(synth.normal(5, "bias", (N,))); aux = _bf(synth.normal(5, "aux", (M, N)))
+    Ad, Bd, bd, xd = A.cuda(), B.cuda(), bias.cuda(), aux.cuda()
+    Cb = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, K, False, Cb, 2, bd, xd, None, None)
+    ref = A.double().numpy() @ B.double().numpy().T + bias.double().numpy() + aux.double().numpy()
+    assert max_norm_err(Cb.double().cpu().numpy(), ref) < 6e-3
+    codes = torch.full((M, N), 55, dtype=torch.int8, device="cuda")
+    scales = torch.full((M * N // 64,), -3.0, dtype=torch.float32, device="cuda")
+    _splitk_call(lib, M, N, K, Ad, K, Bd, K, False, codes, 6, bd, xd, scales, None)
+    c2 = torch.empty(M * N, dtype=torch.int8, device="cuda"); s2 = torch.empty_like(scales)
+    sw.swarm_codec_encode(Cb.reshape(-1), c2, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(codes.reshape(-1), c2) and torch.equal(scales.view(torch.int32), s2.view(torch.int32))
+    rc, rs = ocodec.encode(Cb.float().cpu().numpy().reshape(-1))      # and the oracle codec on the same bits
+    assert np.array_equal(rc, c2.cpu().numpy()) and np.array_equal(rs, s2.cpu().numpy())

@@ -102,3 +102,25 @@ def test_gpt2_vocabulary_workload_shapes():
     small = wl.replace(d_model=64, tokens=100)
     tokens, targets, x, _ = synth.make_head_inputs(small)
     assert tokens.min() >= 0 and tokens.max() < wl.vocab and targets.max() < wl.vocab
+
+
+def test_fp32_agrees_with_fp64():
+    """The full-size GPU parity test runs this oracle in fp32; its fp32 results stay within 2e-5 (max-normalised;
+    the loss relatively) of the fp64 ones on a vocabulary of a few thousand rows."""
+    wl = synth.HeadWorkload("p", "f32", 256, 3001, 3008, 96, seed=21)
+    table, head = synth.make_head_params(wl)
+    head["w_vocab"][:wl.vocab] *= 10.0
+    tokens, targets, x, dxe = synth.make_head_inputs(wl)
+    out = {}
+    for dt in (np.float64, np.float32):
+        hp = {k: v.astype(dt) for k, v in head.items()}
+        g = {k: np.zeros(v.shape, dtype=dt) for k, v in head.items()}
+        res = oh.head_loss_backward(x, targets, hp, wl.vocab, g, wl.ln_eps, dt)
+        assert res[2].dtype == dt and res[1].dtype == dt
+        out[dt] = (res, g)
+    (r64, g64), (r32, g32) = out[np.float64], out[np.float32]
+    flat = lambda r: [np.asarray(t, dtype=np.float64) for t in (r if isinstance(r, (tuple, list)) else (r,))]
+    for a, b in zip(flat(r32), flat(r64)):
+        assert np.max(np.abs(a - b)) <= 2e-5 * max(np.max(np.abs(b)), 1e-30)
+    for k in g64:
+        assert np.max(np.abs(g32[k].astype(np.float64) - g64[k])) <= 2e-5 * np.max(np.abs(g64[k])), k

@@ -369,4 +369,14 @@ def test_section43_parameter_count():
     per_stage = sum(int(np.prod(shapes[k])) for k in ("w_qkv", "w_o", "w_1", "w_2"))
     assert per_stage == 4 * d * d + 3 * d * wl.d_ffn
     model = stages * per_stage + vocab * d           # embedding shared with the LM head
-    assert abs(model - total) / total < 0.005
+    # the paper prints three digits (1.01 B): half a unit of the last digit
+    close = lambda n: abs(n - total) <= 0.005e9
+    assert close(model)
+    # what the printed total excludes: a plain GeLU feed-forward (two d x f matrices), no vocabulary matrix,
+    # two untied vocabulary matrices, unshared layers, or another width
+    f = wl.d_ffn
+    assert not close(stages * (4 * d * d + 2 * d * f) + vocab * d)
+    assert not close(stages * per_stage)
+    assert not close(stages * per_stage + 2 * vocab * d)
+    assert not close(stages * shared * per_stage + vocab * d)
+    assert not close(stages * (4 * (d // 2) ** 2 + 3 * (d // 2) * f) + vocab * d)
