@@ -34,6 +34,145 @@ def measured_traffic(workload, kernel="gemm_bf16"):
         return None
 
 
+def attainable_peak():
+    """TFLOP/s that a loop of nothing but MFMAs on random bf16 operands sustains on this chip (committed
+    micro-benchmark summary; None if there is none): the ceiling the power budget leaves under the nominal peak."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "mfma_rate_microbench.json")) as f:
+            return float(json.load(f)["attainable_tflops_random_16x16x32"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+EPI_NAMES = {0: "store", 1: "bias", 2: "bias+residual", 3: "bias+gelu", 4: "x gelu'", 5: "fp32 +=", 6: "bias+residual->int8",
+             7: "bias+rotary", 8: "x geglu'", 9: "bias+geglu"}
+
+
+def timed_steps(step, steps, warmup):
+    """W warm-up steps, then exactly K steps between two synchronisations (mean from the host clock) with an event
+    pair round every step on the launch stream (median and min)."""
+    import torch
+    for _ in range(warmup):
+        step()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    mean_ms = (time.perf_counter() - t0) * 1e3 / steps
+    per = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    return mean_ms, per[len(per) // 2], per[0]
+
+
+def gemm_roofline(step, steps, ms_per_step, workload):
+    """Roofline of the dominant kernel (the bf16 MFMA GEMM): the same step run through the instrumented build of the
+    library, whose GEMM dispatcher records an event pair on the launch stream round every GEMM launch."""
+    import paper_2301_11913_amd as sw
+    with sw.using_hooks_library() as lib:
+        lib.swarm_kernel_timing_enable.restype = C.c_int
+        lib.swarm_kernel_timing_collect_launches.restype = C.c_int
+        lib.swarm_kernel_timing_collect_launches.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                                             C.POINTER(C.c_double), C.POINTER(C.c_int), C.c_int]
+        step()                                             # first call through this build (sets LDS sizes)
+        import torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(min(steps, 5)):
+            step()
+        torch.cuda.synchronize()
+        ms_hooks = (time.perf_counter() - t0) * 1e3 / min(steps, 5)
+        room = 8192
+        per_ms, shapes = (C.c_double * room)(), (C.c_int * (6 * room))()
+        tot_ms, tot_fl, launches, by_shape = 0.0, 0.0, 0, {}
+        for _ in range(steps):
+            lib.swarm_kernel_timing_enable(1)
+            step()
+            ms, fl = C.c_double(), C.c_double()
+            nl = lib.swarm_kernel_timing_collect_launches(C.byref(ms), C.byref(fl), per_ms, shapes, room)
+            tot_ms += ms.value; tot_fl += fl.value; launches += nl
+            for i in range(min(nl, room)):
+                key = tuple(shapes[6 * i:6 * i + 6])
+                e = by_shape.setdefault(key, [0, 0.0])
+                e[0] += 1; e[1] += per_ms[i]
+        lib.swarm_kernel_timing_enable(0)
+    achieved = tot_fl / (tot_ms * 1e-3) / 1e12
+    table = []
+    for (M, N, K, at, bt, epi), (cnt, ms) in sorted(by_shape.items(), key=lambda kv: -kv[1][1]):
+        tf = 2.0 * M * N * K * cnt / (ms * 1e-3) / 1e12
+        table.append({"M": M, "N": N, "K": K, "layout": "wgrad" if at else ("dgrad" if bt else "forward"),
+                      "epilogue": EPI_NAMES.get(epi, str(epi)), "launches_per_step": cnt // steps,
+                      "avg_us": round(ms * 1e3 / cnt, 1), "TFLOP/s": round(tf, 1),
+                      "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 3)})
+    out = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
+           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+           "traffic": measured_traffic(workload), "launches_per_step": launches // steps,
+           "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
+           "gemm_share_of_step": round(tot_ms / steps / ms_per_step, 3),
+           "ms_per_step_instrumented_build": round(ms_hooks, 4), "by_shape": table}
+    att = attainable_peak()
+    if att:
+        out["attainable_peak"] = att
+        out["frac_of_attainable"] = round(achieved / att, 4)
+    return out
+
+
+def codec_rates(wl, x_src, modes):
+    """The stand-alone codec kernels on the workload's boundary tensor: HBM-cold (rotating through > 1.5 GiB of
+    buffer sets, beyond the 256 MB last-level cache) and cache-warm (one buffer set).  Algorithmic bytes: element +
+    code + scale / 64.  Times are launch-inclusive (back-to-back launches between two events on the launch stream);
+    the kernel durations that rocprofv3 reports for the same launches are in profiles/ and are attached when there."""
+    import torch
+    import paper_2301_11913_amd as sw
+    dev = x_src.device
+    n = x_src.numel()
+    es = x_src.element_size()
+    byts = n * (es + 1 + 4.0 / 64)
+    nset = max(2, int((1.5 * (1 << 30)) // byts) + 1) if "cold" in modes else 1
+    xs = [torch.empty_like(x_src).copy_(x_src) for _ in range(nset)]
+    cs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nset)]
+    ss = [torch.empty(n // 64, dtype=torch.float32, device=dev) for _ in range(nset)]
+    codec = {"elements": n, "bytes_per_call": byts, "peak_GBps": HBM_PEAK_GBS}
+    for name, fn in (("encode", lambda i: sw.swarm_codec_encode(xs[i], cs[i], ss[i])),
+                     ("decode", lambda i: sw.swarm_codec_decode(cs[i], ss[i], xs[i]))):
+        for mode in modes:
+            idx = list(range(nset)) * 3 if mode == "cold" else [0] * 50
+            for i in idx[:nset]:
+                fn(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in idx:
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / len(idx)
+            codec["%s_%s_us" % (name, mode)] = round(us, 2)
+            codec["%s_%s_GBps" % (name, mode)] = round(byts / us / 1e3, 1)
+    if "cold" in modes:
+        codec["frac_of_hbm_peak_cold"] = {"encode": round(codec["encode_cold_GBps"] / HBM_PEAK_GBS, 3),
+                                          "decode": round(codec["decode_cold_GBps"] / HBM_PEAK_GBS, 3)}
+    try:
+        with open(os.path.join(ROOT, "profiles", "codec_%s_kernel_durations.json" % wl.name)) as f:
+            codec["rocprofv3_kernel_durations"] = json.load(f)
+    except (OSError, ValueError):
+        pass
+    return codec
+
+
+def blas_threads():
+    """Threads of the BLAS that numpy's matmul actually uses (the oracle's only library primitive)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:
+        pass
+    return os.cpu_count() or 1
+
+
 def model_flops(wl):
     """Paper convention (Table 6: 6 * parameters * tokens for fwd+bwd) plus the causal attention term."""
     T, d, f, S, B = wl.tokens, wl.d_model, wl.d_ffn, wl.seq, wl.batch
@@ -43,35 +182,55 @@ def model_flops(wl):
 
 
 def cpu_baseline(wl):
-    """The oracle as it stands, on the host cores, on a bounded sample of the workload:
-    one sequence (batch 1) through ONE block application, forward + backward, plus the codec on
-    that sequence's boundary tensors.  Scaled to the workload's block count."""
+    """The oracle as it stands, on the host cores, on bounded samples of the workload.  `value`: one sequence
+    (batch 1) through ONE block application, forward + recomputing backward (+ the codec on that sequence's
+    boundary tensors), in fp32 with all BLAS threads, scaled to the workload's block count.  Beside it: the same
+    sample in fp64, a 512-token sample on one thread, and the oracle codec's own rate."""
     import numpy as np
     import swarm_synth as synth
     from oracle import stage as osg, codec as ocodec
-    seq = min(wl.seq, 2048)
-    sample = wl.replace(batch=1, seq=seq, n_layers=1, n_repeat=1)
-    params, x, G = synth.make_params(sample), synth.make_x_in(sample), synth.make_grad_out(sample)
-    t0 = time.perf_counter()
-    if wl.boundary_codec:
-        cx, sx = ocodec.encode(x.reshape(-1))
-        x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(x.shape)
-        cg, sg = ocodec.encode(G.reshape(-1))
-        G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(G.shape)
-    y = osg.stage_forward(params, x, sample.n_heads, 1, sample.ln_eps, np.float64, kind=sample.block)
-    grads = osg.zero_grads(params, np.float64)
-    gin = osg.stage_backward(params, x, G, grads, sample.n_heads, 1, sample.ln_eps, np.float64,
-                             kind=sample.block)
-    if wl.boundary_codec:
-        ocodec.encode(y.astype(np.float32).reshape(-1))
-        ocodec.encode(gin.astype(np.float32).reshape(-1))
-    dt = time.perf_counter() - t0
+    from threadpoolctl import threadpool_limits
     apps = wl.n_layers * wl.n_repeat
-    import torch
-    return {"value": seq / (dt * apps), "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": "fp64 numpy oracle, 1 sequence of %d tokens through 1 of %d block applications "
-                      "(fwd + recomputing bwd%s), %.1f s; rate divided by the block count"
-                      % (seq, apps, " + codec" if wl.boundary_codec else "", dt)}
+
+    def run(seq, dt):
+        sample = wl.replace(batch=1, seq=seq, n_layers=1, n_repeat=1)
+        params, x, G = synth.make_params(sample), synth.make_x_in(sample), synth.make_grad_out(sample)
+        t0 = time.perf_counter()
+        if wl.boundary_codec:
+            cx, sx = ocodec.encode(x.reshape(-1))
+            x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(x.shape)
+            cg, sg = ocodec.encode(G.reshape(-1))
+            G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(G.shape)
+        y = osg.stage_forward(params, x, sample.n_heads, 1, sample.ln_eps, dt, kind=sample.block)
+        grads = osg.zero_grads(params, dt)
+        gin = osg.stage_backward(params, x, G, grads, sample.n_heads, 1, sample.ln_eps, dt, kind=sample.block)
+        if wl.boundary_codec:
+            ocodec.encode(y.astype(np.float32).reshape(-1))
+            ocodec.encode(gin.astype(np.float32).reshape(-1))
+        return time.perf_counter() - t0
+
+    seq = min(wl.seq, 2048)
+    cores = blas_threads()
+    t32 = run(seq, np.float32)
+    t64 = run(seq, np.float64)
+    small = min(seq, 512)
+    with threadpool_limits(limits=1):
+        t1 = run(small, np.float32)
+    # the oracle codec alone (numpy, one thread): bytes moved = element + code + scale / 64, as for the GPU figure
+    xs = synth.make_x_in(wl.replace(batch=1, seq=seq)).reshape(-1)
+    es = 2 if wl.dtype == "bf16" else 4
+    t0 = time.perf_counter(); codes, scales = ocodec.encode(xs); te = time.perf_counter() - t0
+    t0 = time.perf_counter(); ocodec.decode(codes, scales, out="bf16" if wl.dtype == "bf16" else "f32"); td = time.perf_counter() - t0
+    byts = xs.size * (es + 1 + 4.0 / 64)
+    return {"value": seq / (t32 * apps), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "fp32 numpy oracle, 1 sequence of %d tokens through 1 of %d block applications (fwd + "
+                      "recomputing bwd%s), %.1f s on %d BLAS threads; rate divided by the block count"
+                      % (seq, apps, " + codec" if wl.boundary_codec else "", t32, cores),
+            "fp64_all_cores_tokens_per_s": seq / (t64 * apps), "fp64_sample_s": round(t64, 2),
+            "fp32_one_thread_tokens_per_s": small / (t1 * apps),
+            "one_thread_sample": "1 sequence of %d tokens, %.1f s" % (small, t1),
+            "codec_encode_GBps": byts / te / 1e9, "codec_decode_GBps": byts / td / 1e9,
+            "codec_sample": "oracle codec on %d elements, encode %.2f s, decode %.2f s" % (xs.size, te, td)}
 
 
 def bench_boundary(args):
@@ -108,35 +267,12 @@ def bench_boundary(args):
         sw.swarm_decompress_backward(cfg, dec, z, dx, dz, gd, ws)
         sw.swarm_compress_backward(cfg, comp, y, dz, dy, gc, ws)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    lib.swarm_kernel_timing_enable.restype = C.c_int
-    lib.swarm_kernel_timing_collect.restype = C.c_int
-    lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
-    tot_ms, tot_fl, launches = 0.0, 0.0, 0
-    for _ in range(args.steps):
-        lib.swarm_kernel_timing_enable(1)
-        step()
-        ms, fl = C.c_double(), C.c_double()
-        nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
-        tot_ms += ms.value; tot_fl += fl.value; launches += nl
-    lib.swarm_kernel_timing_enable(0)
-    achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
-                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
-                "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
-                "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+    ms_per_step, ms_median, ms_min = timed_steps(step, args.steps, args.warmup)
+    roofline = gemm_roofline(step, args.steps, ms_per_step, wl.name)
     out = {"metric": "boundary layer fwd+bwd tokens/s (sender + receiver halves)",
            "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+           "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+           "ms_per_step_min": round(ms_min, 4), "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
            "config": {"workload": wl.name, "kind": wl.kind, "d_model": m, "d_comp": c, "tokens": T},
            "roofline": roofline}
@@ -151,7 +287,7 @@ def bench_boundary(args):
         dzz = ob.decompress_backward(zz, dxs, dp, {k: np.zeros(v.shape) for k, v in dp.items()}, wl.ln_eps)
         ob.compress_backward(ys, dzz, cp, {k: np.zeros(v.shape) for k, v in cp.items()}, wl.kind, c, wl.ln_eps)
         dts = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": torch.get_num_threads(),
+        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": blas_threads(),
                                "kind": "oracle", "sample": "fp64 numpy oracle, %d tokens through both halves "
                                "(fwd + recomputing bwd), %.1f s" % (sample.tokens, dts)}
     print(json.dumps(out))
@@ -192,35 +328,12 @@ def bench_head(args):
         sw.swarm_head_loss_backward(cfg, head, x_head, targets, loss, None, dx_head, grads, ws)   # last stage
         sw.swarm_embedding_backward(tokens, dx_emb, V, grad_table)                        # first stage
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    lib.swarm_kernel_timing_enable.restype = C.c_int
-    lib.swarm_kernel_timing_collect.restype = C.c_int
-    lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
-    tot_ms, tot_fl, launches = 0.0, 0.0, 0
-    for _ in range(args.steps):
-        lib.swarm_kernel_timing_enable(1)
-        step()
-        ms, fl = C.c_double(), C.c_double()
-        nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
-        tot_ms += ms.value; tot_fl += fl.value; launches += nl
-    lib.swarm_kernel_timing_enable(0)
-    achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
-                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
-                "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,
-                "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+    ms_per_step, ms_median, ms_min = timed_steps(step, args.steps, args.warmup)
+    roofline = gemm_roofline(step, args.steps, ms_per_step, wl.name)
     out = {"metric": "embedding fwd+bwd and LM head loss+bwd tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+           "ms_per_step_min": round(ms_min, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": wl.dtype, "data": "synthetic",
            "config": {"workload": wl.name, "d_model": d, "vocab": V, "vocab_rows": Vp, "tokens": T},
            "loss": round(float(loss.item()), 4), "roofline": roofline}
@@ -234,7 +347,7 @@ def bench_head(args):
         oh.head_loss_backward(xs, tg, hp, V, {k: np.zeros(v.shape) for k, v in hp.items()}, wl.ln_eps)
         oh.embedding_backward(tk, dxe, np.zeros(tab.shape))
         dts = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": torch.get_num_threads(),
+        out["cpu_baseline"] = {"value": sample.tokens / dts, "unit": "tokens/s", "cores": blas_threads(),
                                "kind": "oracle", "sample": "fp64 numpy oracle, %d tokens (embedding fwd + bwd, head "
                                "loss + bwd), %.1f s" % (sample.tokens, dts)}
     print(json.dumps(out))
@@ -334,6 +447,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused-codec", action="store_true",
                     help="call swarm_codec_decode/encode around the stage instead of the *_coded entry points")
+    ap.add_argument("--codec-only", choices=["cold", "warm"], default=None,
+                    help="run only the stand-alone codec kernels on the workload's boundary tensor, HBM-cold or "
+                         "cache-warm (for a rocprofv3 --kernel-trace run whose kernel durations are the codec figure)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -372,6 +488,14 @@ def main():
     shape = (wl.batch, wl.seq, wl.d_model)
     n = wl.tokens * wl.d_model
     x_src, g_src = rn(shape, 1.0), rn(shape, wl.grad_sigma)
+    if args.codec_only:
+        codec = codec_rates(wl, x_src, (args.codec_only,))
+        m = args.codec_only
+        print(json.dumps({"metric": "int8 boundary codec GB/s (%s)" % ("HBM-cold" if m == "cold" else "cache-warm"),
+                          "value": codec["encode_%s_GBps" % m], "unit": "GB/s", "n_gpus": 1, "higher_is_better": True,
+                          "dtype": wl.dtype, "data": "synthetic", "config": {"workload": wl.name, "mode": m},
+                          "codec": codec}))
+        return
     cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
                          wl.ln_eps, wl.block)
     ws = torch.empty(max(sw.swarm_stage_coded_workspace_bytes(cfg, True), sw.swarm_stage_coded_workspace_bytes(cfg, False)),
@@ -402,68 +526,14 @@ def main():
             sw.swarm_codec_encode(y, codes["y"], scales["y"])
             sw.swarm_codec_encode(gin, codes["gin"], scales["gin"])
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step, ms_median, ms_min = timed_steps(step, args.steps, args.warmup)
 
-    # roofline of the dominant kernel (the bf16 MFMA GEMM): event pairs on the launch stream around
-    # every GEMM launch of the same K steps
-    roofline = None
-    if wl.dtype == "bf16":
-        lib.swarm_kernel_timing_enable.restype = C.c_int
-        lib.swarm_kernel_timing_collect.restype = C.c_int
-        lib.swarm_kernel_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double)]
-        tot_ms, tot_fl, launches = 0.0, 0.0, 0
-        for _ in range(args.steps):
-            lib.swarm_kernel_timing_enable(1)
-            step()
-            ms, fl = C.c_double(), C.c_double()
-            nl = lib.swarm_kernel_timing_collect(C.byref(ms), C.byref(fl))
-            tot_ms += ms.value; tot_fl += fl.value; launches += nl
-        lib.swarm_kernel_timing_enable(0)
-        achieved = tot_fl / (tot_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": measured_traffic(wl.name), "launches_per_step": launches // args.steps,
-                    "avg_launch_us": round(tot_ms * 1e3 / launches, 1),
-                    "flops_per_launch": tot_fl / launches,
-                    "gemm_share_of_step": round(tot_ms / args.steps / ms_per_step, 3)}
+    roofline = gemm_roofline(step, args.steps, ms_per_step, wl.name) if wl.dtype == "bf16" else None
 
-    # codec alone on the boundary tensor, HBM-cold (rotating through > 1 GiB of buffer sets, beyond the
-    # 256 MB last-level cache) and cache-warm (one buffer set); algorithmic bytes: element + code + scale/64
-    codec = None
-    if wl.boundary_codec:
-        es = 2 if wl.dtype == "bf16" else 4
-        byts = n * (es + 1 + 4.0 / 64)
-        nset = max(2, int((1.5 * (1 << 30)) // byts) + 1)
-        xs = [torch.empty(shape, dtype=dt, device=dev).copy_(x_src) for _ in range(nset)]
-        cs = [torch.empty(n, dtype=torch.int8, device=dev) for _ in range(nset)]
-        ss = [torch.empty(n // 64, dtype=torch.float32, device=dev) for _ in range(nset)]
-        codec = {"elements": n, "bytes_per_call": byts, "peak_GBps": 8000.0}
-        for name, fn in (("encode", lambda i: sw.swarm_codec_encode(xs[i], cs[i], ss[i])),
-                         ("decode", lambda i: sw.swarm_codec_decode(cs[i], ss[i], xs[i]))):
-            for mode, idx in (("cold", list(range(nset)) * 3), ("warm", [0] * 50)):
-                for i in idx[:nset]:
-                    fn(i)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in idx:
-                    fn(i)
-                e1.record()
-                torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / len(idx)
-                codec["%s_%s_us" % (name, mode)] = round(us, 2)
-                codec["%s_%s_GBps" % (name, mode)] = round(byts / us / 1e3, 1)
-        codec["frac_of_hbm_peak_cold"] = {"encode": round(codec["encode_cold_GBps"] / 8000.0, 3),
-                                          "decode": round(codec["decode_cold_GBps"] / 8000.0, 3)}
-        codec["stage_time_over_codec_time"] = round(ms_per_step * 1e3 / (2 * codec["encode_cold_us"] + 2 * codec["decode_cold_us"]), 1)
-        del xs, cs, ss
+    codec = codec_rates(wl, x_src, ("cold", "warm"))
+    # a peer decodes x_in and grad_out and encodes x_out and grad_in per microbatch (for the workloads whose step
+    # runs without the codec this is the compute-to-boundary ratio of Section 3.1 on the same boundary tensor)
+    codec["stage_time_over_codec_time"] = round(ms_per_step * 1e3 / (2 * codec["encode_cold_us"] + 2 * codec["decode_cold_us"]), 1)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -476,7 +546,8 @@ def main():
     tokens_per_s = wl.tokens / (ms_per_step * 1e-3)
     out = {"metric": "stage fwd+bwd tokens/s (+ int8 boundary codec)", "value": round(tokens_per_s, 1),
            "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "ms_per_step": round(ms_per_step, 4), "ms_per_step_median": round(ms_median, 4),
+           "ms_per_step_min": round(ms_min, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": wl.dtype, "data": "synthetic",
            "config": {"workload": wl.name, "block": wl.block, "d_model": wl.d_model, "n_heads": wl.n_heads, "d_ffn": wl.d_ffn,
                       "seq": wl.seq, "microbatch": wl.batch, "blocks": wl.n_layers, "repeat": wl.n_repeat,

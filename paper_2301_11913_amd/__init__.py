@@ -6,6 +6,7 @@ device memory and streams.  There is no CPU fallback: a missing library raises.
 """
 from .binding import (  # noqa: F401
     SWARM_F32, SWARM_BF16, SWARM_BLOCK_GELU, SWARM_BLOCK_ROTARY_GEGLU, SwarmError, StageConfig, lib_path, load_library,
+    hooks_lib_path, load_hooks_library, using_hooks_library,
     swarm_stage_workspace_bytes, swarm_stage_forward, swarm_stage_backward,
     swarm_codec_encode, swarm_codec_decode, swarm_status_string,
     swarm_stage_coded_workspace_bytes, swarm_stage_forward_coded, swarm_stage_backward_coded,

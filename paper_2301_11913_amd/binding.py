@@ -1,6 +1,7 @@
 """ctypes binding of the C ABI in include/swarm_stage.h (argument marshalling only)."""
 from __future__ import annotations
 
+import contextlib
 import ctypes as C
 import os
 from typing import Dict, List, Optional, Sequence
@@ -106,15 +107,46 @@ def lib_path() -> str:
     return os.environ.get("SWARM_STAGE_LIB", os.path.join(_PKG, "libswarm_stage.so"))
 
 
+def hooks_lib_path() -> str:
+    return os.environ.get("SWARM_HOOKS_LIB", os.path.join(_PKG, "libswarm_hooks.so"))
+
+
 _lib = None
+_hooks_lib = None
 
 
 def load_library():
-    """Load libswarm_stage.so; raises if it has not been built (there is no fallback)."""
+    """Load libswarm_stage.so; raises if it has not been built (there is no fallback).  Inside a
+    `with using_hooks_library():` block the instrumented build is returned instead."""
     global _lib
     if _lib is not None:
         return _lib
-    path = lib_path()
+    _lib = _open(lib_path())
+    return _lib
+
+
+def load_hooks_library():
+    """Load libswarm_hooks.so: the same sources plus the single-kernel entry points (swarm_kernel_*), the per-launch
+    GEMM timer and the micro-benchmarks.  For tests and measurements only; the product is libswarm_stage.so."""
+    global _hooks_lib
+    if _hooks_lib is None:
+        _hooks_lib = _open(hooks_lib_path())
+    return _hooks_lib
+
+
+@contextlib.contextmanager
+def using_hooks_library():
+    """Route every binding call inside the block to libswarm_hooks.so (bench.py times GEMM launches this way)."""
+    global _lib
+    product = load_library()
+    _lib = load_hooks_library()
+    try:
+        yield _lib
+    finally:
+        _lib = product
+
+
+def _open(path):
     if not os.path.exists(path):
         raise FileNotFoundError(
             "%s not found: build it with `python -m paper_2301_11913_amd.build` "
@@ -183,7 +215,6 @@ def load_library():
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.swarm_status_string.restype = C.c_char_p
     lib.swarm_status_string.argtypes = [C.c_int]
-    _lib = lib
     return lib
 
 

@@ -1,10 +1,12 @@
-"""Build libswarm_stage.so (gfx950) in-tree with hipcc.
+"""Build the two gfx950 libraries in-tree with hipcc.
 
     python -m paper_2301_11913_amd.build
 
-Every translation unit under csrc/ is compiled to an object under _build/ and
-linked into paper_2301_11913_amd/libswarm_stage.so.  hipcc cross-compiles, so
-no GPU is needed to build.
+libswarm_stage.so is the product: every translation unit under csrc/ except the hook files, compiled to an object
+under _build/ and linked.  libswarm_hooks.so is the instrumented build for tests and measurements: the same objects,
+with the GEMM sources compiled a second time under -DSWARM_KERNEL_HOOKS (per-launch event timer, optional phase
+stamps), plus kernel_hooks.hip (single-kernel entry points) and microbench.hip.  hipcc cross-compiles, so no GPU is
+needed to build.
 """
 from __future__ import annotations
 
@@ -18,6 +20,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libswarm_stage.so")
+OUT_HOOKS = os.path.join(PKG, "libswarm_hooks.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -29,9 +32,17 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", os.path.j
 EXTRA = {"codec.hip": ["-ffp-contract=off"]}
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(BUILD_DIR, os.path.basename(src) + ".o")
+# files that exist only in the instrumented build, and files that are compiled a second time for it
+HOOK_ONLY = ("kernel_hooks.hip", "microbench.hip")
+HOOK_VARIANTS = ("gemm_bf16.hip", "gemm_bf16_dma.hip")
+
+
+def _compile(job) -> str:
+    src, hooks = job
+    obj = _obj(src, hooks)
     cmd = [HIPCC, "-c", src, "-o", obj] + COMMON + EXTRA.get(os.path.basename(src), [])
+    if hooks:
+        cmd.append("-DSWARM_KERNEL_HOOKS")
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, " ".join(cmd), r.stderr[-8000:]))
@@ -39,18 +50,32 @@ def _compile(src: str) -> str:
     return warn
 
 
-def build(verbose: bool = False) -> str:
-    os.makedirs(BUILD_DIR, exist_ok=True)
-    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        for src, warn in zip(srcs, ex.map(_compile, srcs)):
-            if verbose and warn:
-                print("[%s]\n%s" % (os.path.basename(src), warn), file=sys.stderr)
-    objs = [os.path.join(BUILD_DIR, os.path.basename(s) + ".o") for s in srcs]
-    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT] + objs
+def _obj(src: str, hooks: bool) -> str:
+    return os.path.join(BUILD_DIR, os.path.basename(src) + (".hooks.o" if hooks else ".o"))
+
+
+def _link(out: str, objs) -> None:
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + list(objs)
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s" % r.stderr[-8000:])
+
+
+def build(verbose: bool = False) -> str:
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    name = os.path.basename
+    # longest translation units first, so the pool does not end on one of them
+    jobs = [(s, True) for s in srcs if name(s) in HOOK_VARIANTS] + \
+           [(s, False) for s in srcs if name(s) not in HOOK_ONLY] + [(s, True) for s in srcs if name(s) in HOOK_ONLY]
+    jobs.sort(key=lambda j: -os.path.getsize(j[0]))
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
+        for (src, hooks), warn in zip(jobs, ex.map(_compile, jobs)):
+            if verbose and warn:
+                print("[%s%s]\n%s" % (name(src), " (hooks)" if hooks else "", warn), file=sys.stderr)
+    product = [s for s in srcs if name(s) not in HOOK_ONLY]
+    _link(OUT, [_obj(s, False) for s in product])
+    _link(OUT_HOOKS, [_obj(s, name(s) in HOOK_VARIANTS) for s in product] + [_obj(s, True) for s in srcs if name(s) in HOOK_ONLY])
     return OUT
 
 

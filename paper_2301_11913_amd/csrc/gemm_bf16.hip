@@ -202,15 +202,18 @@ swarm_status launch_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t st) {
   return SWARM_ERR_SHAPE;
 }
 
-// Optional per-launch timing of the MFMA GEMM (off by default): an event pair on the launch stream
-// around every launch, read back by swarm_kernel_timing_collect().  Measurement plumbing only.
+#ifdef SWARM_KERNEL_HOOKS
+// Per-launch timing of the MFMA GEMM, compiled into the instrumented build only (libswarm_hooks.so; off until
+// enabled): an event pair on the launch stream around every launch, read back by swarm_kernel_timing_collect().
 struct GemmTimer {
   static constexpr int kMax = 8192;
   bool enabled = false;
   int used = 0;
   std::vector<hipEvent_t> ev;      // 2 per launch
   std::vector<double> flops;
+  std::vector<int> shape;          // 6 per launch: M, N, K, a_trans, b_trans, epilogue
 } g_timer;
+#endif
 
 }  // namespace
 
@@ -218,13 +221,19 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st);
 swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st);
 
 swarm_status gemm_bf16(const GemmArgs& g, hipStream_t st) {
-  if (!g_timer.enabled || g_timer.used >= GemmTimer::kMax) return gemm_bf16_launch(g, st);
-  const int i = g_timer.used++;
-  g_timer.flops[i] = 2.0 * g.M * g.N * g.K;
-  (void)hipEventRecord(g_timer.ev[2 * i], st);
-  swarm_status s = gemm_bf16_launch(g, st);
-  (void)hipEventRecord(g_timer.ev[2 * i + 1], st);
-  return s;
+#ifdef SWARM_KERNEL_HOOKS
+  if (g_timer.enabled && g_timer.used < GemmTimer::kMax) {
+    const int i = g_timer.used++;
+    g_timer.flops[i] = 2.0 * g.M * g.N * g.K;
+    int* sh = &g_timer.shape[6 * i];
+    sh[0] = g.M; sh[1] = g.N; sh[2] = g.K; sh[3] = g.a_trans; sh[4] = g.b_trans; sh[5] = g.epilogue;
+    (void)hipEventRecord(g_timer.ev[2 * i], st);
+    swarm_status s = gemm_bf16_launch(g, st);
+    (void)hipEventRecord(g_timer.ev[2 * i + 1], st);
+    return s;
+  }
+#endif
+  return gemm_bf16_launch(g, st);
 }
 
 swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
@@ -255,7 +264,7 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
-  k.ksplit = 1; k.part = nullptr; k.stream = 0;
+  k.ksplit = 1; k.part = nullptr; k.stream = 0; k.stamps = nullptr;
   const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= 160) {
     k.tiles_m = (g.M + 255) / 256; k.tiles_n = (g.N + 255) / 256;
@@ -271,12 +280,14 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
 
 }  // namespace swarm
 
+#ifdef SWARM_KERNEL_HOOKS
 // Turn per-launch GEMM timing on (creates the event pool once) or off; resets the counters.
 extern "C" int swarm_kernel_timing_enable(int on) {
   using namespace swarm;
   if (on && g_timer.ev.empty()) {
     g_timer.ev.resize(2 * GemmTimer::kMax);
     g_timer.flops.resize(GemmTimer::kMax);
+    g_timer.shape.resize(6 * GemmTimer::kMax);
     for (auto& e : g_timer.ev)
       if (hipEventCreate(&e) != hipSuccess) return -1;
   }
@@ -285,8 +296,11 @@ extern "C" int swarm_kernel_timing_enable(int on) {
   return 0;
 }
 
-// Synchronises, then returns the number of timed launches and their summed duration / flops.
-extern "C" int swarm_kernel_timing_collect(double* total_ms, double* total_flops) {
+// Synchronises, then returns the number of timed launches and their summed duration / flops.  With per_launch_ms
+// and shapes not NULL (room for `room` launches: room doubles, 6 * room ints) every launch's duration and its
+// M, N, K, a_trans, b_trans, epilogue are written too.
+extern "C" int swarm_kernel_timing_collect_launches(double* total_ms, double* total_flops, double* per_launch_ms,
+                                                    int* shapes, int room) {
   using namespace swarm;
   double ms = 0, fl = 0;
   for (int i = 0; i < g_timer.used; ++i) {
@@ -295,6 +309,10 @@ extern "C" int swarm_kernel_timing_collect(double* total_ms, double* total_flops
     if (hipEventElapsedTime(&t, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]) != hipSuccess) return -1;
     ms += t;
     fl += g_timer.flops[i];
+    if (per_launch_ms && shapes && i < room) {
+      per_launch_ms[i] = t;
+      for (int k = 0; k < 6; ++k) shapes[6 * i + k] = g_timer.shape[6 * i + k];
+    }
   }
   *total_ms = ms;
   *total_flops = fl;
@@ -302,3 +320,7 @@ extern "C" int swarm_kernel_timing_collect(double* total_ms, double* total_flops
   g_timer.used = 0;
   return n;
 }
+extern "C" int swarm_kernel_timing_collect(double* total_ms, double* total_flops) {
+  return swarm_kernel_timing_collect_launches(total_ms, total_flops, nullptr, nullptr, 0);
+}
+#endif  // SWARM_KERNEL_HOOKS

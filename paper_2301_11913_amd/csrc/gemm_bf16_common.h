@@ -26,6 +26,7 @@ struct KArgs {
   int stream;    // != 0: the epilogue's global accesses are non-temporal (see store_stream)
   int ksplit;    // > 1: the grid holds ksplit workgroups per tile, each takes K / ksplit and stores its fp32 partial
   float* part;   //      tile sums to part + index * M * N (a second kernel adds them and applies the epilogue)
+  long long* stamps;   // instrumented build only (nullptr otherwise): 16 words per workgroup, see gemm_bf16_k32_kernel
 };
 
 constexpr int EPI_PART_F32 = 100;   // kernel-internal: C (fp32, ldc = N) = acc, no read

@@ -371,6 +371,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
   static_assert(DBK == 64 && NS == 2, "two 32-deep sub-steps per slice, two stages");
   static_assert(FN >= 2 && FM >= FN + 2 && 2 * IPW + FN + 2 <= FM * FN, "read / load slots of a sub-step");
   extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+#ifdef SWARM_KERNEL_HOOKS
+  // Instrumented build: wall-clock stamps (100 MHz counter) at the start, at the first barrier, behind the loop
+  // and when the epilogue's stores have left; written only when the caller asks (p.stamps).
+  long long stamp[4], cyc[2];
+  stamp[0] = wall_clock64();
+#endif
 
   int tile_m, tile_n;
   if (p.ksplit > 1) {
@@ -413,6 +419,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
   }
   wait_vmcnt<IPW>();
   __builtin_amdgcn_s_barrier();
+#ifdef SWARM_KERNEL_HOOKS
+  stamp[1] = wall_clock64();
+  cyc[0] = clock64();
+#endif
 
   auto read_a = [&](const bf16_raw* sA, int i, int kk) __attribute__((always_inline)) {
     if constexpr (A_T) return frag_trans16<BM>(sA, wm * WTM + 16 * i, kk, lane);
@@ -477,10 +487,28 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
   wait_vmcnt<0>();
   __builtin_amdgcn_s_waitcnt(0xC07F);
   __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read: the stages become epilogue patches
+#ifdef SWARM_KERNEL_HOOKS
+  stamp[2] = wall_clock64();
+  cyc[1] = clock64();
+#endif
 
   gemm_epilogue<WTM / 32, WTN / 32, false>(p, acc, m0 + wm * WTM, glu ? n0 + wn * (WTN / 2) : n0 + wn * WTN,
                                           lane & 31, lane >> 5,
                                           reinterpret_cast<float*>(lds) + wave * 32 * kEpiPitch);
+#ifdef SWARM_KERNEL_HOOKS
+  if (p.stamps) {
+    wait_vmcnt<0>();   // the stores have left
+    stamp[3] = wall_clock64();
+    if (threadIdx.x == 0) {
+      long long* out = p.stamps + (size_t)blockIdx.x * 16;
+      out[0] = stamp[0]; out[1] = stamp[1]; out[2] = stamp[2]; out[3] = stamp[3];
+      out[4] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID: compute unit, shader engine
+      out[5] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));   // XCC_ID
+      out[6] = tile_m; out[7] = tile_n;
+      out[8] = cyc[1] - cyc[0];   // shader cycles spent in the loop
+    }
+  }
+#endif
 }
 
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
@@ -591,7 +619,7 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
   k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
-  k.ksplit = 1; k.part = nullptr;
+  k.ksplit = 1; k.part = nullptr; k.stamps = g.stamps;
   // An output of at least twice the 32 MB of L2 cannot wait there for its consumer; written (and its residual /
   // pre-activation / gradient rows read) non-temporally it leaves the operand panels in the L2 instead.
   k.stream = (size_t)g.M * g.N * (g.epilogue == EPI_ACCUM_F32 ? 4 : 2) >= ((size_t)64 << 20);

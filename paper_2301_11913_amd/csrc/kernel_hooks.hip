@@ -27,6 +27,20 @@ extern "C" int swarm_kernel_gemm_ws(int M, int N, int K, const void* A, int lda,
   return gemm_bf16(g, (hipStream_t)stream);
 }
 
+// The same again with phase stamps of the 256 x 256 kernel: stamps [workgroups x 16] int64 (device) receive, per
+// workgroup, the 100 MHz wall clock at its start, at the first barrier, behind the loop and when the epilogue's
+// stores have left, then the HW_ID and XCC_ID registers, the tile coordinates and the shader cycles spent in the loop.
+extern "C" int swarm_kernel_gemm_stamped(int M, int N, int K, const void* A, int lda, int a_trans, const void* B,
+                                         int ldb, int b_trans, void* C, int ldc, int epilogue, const void* bias,
+                                         const void* aux, int ldaux, long long* stamps, void* stream) {
+  GemmArgs g{};
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.a_trans = a_trans != 0; g.B = B; g.ldb = ldb;
+  g.b_trans = b_trans != 0; g.C = C; g.ldc = ldc; g.epilogue = epilogue; g.bias = bias; g.aux = aux;
+  g.ldaux = ldaux; g.stamps = stamps;
+  if (M % 256 || N % 256 || (long)(M / 256) * (N / 256) < 160) return SWARM_ERR_SHAPE;   // one 256 x 256 launch only
+  return gemm_bf16(g, (hipStream_t)stream);
+}
+
 extern "C" int swarm_kernel_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int B, int S, int H,
                                           int dh, void* stream) {
   return attention_fwd(qkv, o, lse, B, S, H, dh, dtype != 0, (hipStream_t)stream);

@@ -44,6 +44,7 @@ struct GemmArgs {
   int split;               // EPI_DGEGLU / EPI_BIAS_GEGLU: f, the width of the gate (and of the up) half
   float* splitk_ws;        // optional scratch of splitk_floats floats (>= gemm_splitk_floats(M, N)): lets a product with
   size_t splitk_floats;    // few output tiles and a long K be cut along K (bf16 MFMA kernel only); nullptr: never cut
+  long long* stamps;       // instrumented build only: 16 int64 per workgroup of the 256 x 256 kernel (phase stamps)
 };
 
 // Floats of split-K scratch that a bf16 product with an [M, N] output can make use of (0: it is never cut).

@@ -1,8 +1,8 @@
 // Stage driver: the fixed sequence of kernel launches for one pipeline stage's forward and
 // checkpoint-recomputing backward (paper Section 3.2), plus workspace carving and argument
 // validation.  Host code only; all arithmetic happens in the kernels it launches.
+#include <algorithm>
 #include <cstdlib>
-#include <vector>
 
 #include "kernels.h"
 
@@ -294,9 +294,12 @@ int wgrad_chunk(const Dims& D, int R) {
   return (int)std::max<long long>(1, std::min<long long>(R, kMaxWgradRows / D.T));
 }
 
+// Workspace layout of the backward call.  Plain pointers and pitches only: the plan lives on the caller's stack and
+// the intermediates of application i are found by arithmetic (saved_at), so a call touches no host heap.
 struct BwdPlan {
-  std::vector<Saved> saved;
-  std::vector<void*> xbuf;   // inputs of applications 1..apps-1
+  char *a_all, *o_all, *c_all, *g_all;   // [apps] slots of [T,d] x3 and [T,f]: right-hand operands of the wgrads
+  char* app_slots;                        // [apps] slots of app_pitch bytes: qkv, h, u, row statistics, lse, input
+  size_t app_pitch, off_h, off_u, off_stats, off_lse, off_x;
   BwdTemps t;
   char *du_slots, *dh_slots, *dqkv_slots;   // [R] slots of [T,f1], [T,d], [T,3d]: one per application of a set
   char* dys[2];              // [R] slots of [T,d] (gradient of each application's output), by parameter-set parity
@@ -307,25 +310,24 @@ struct BwdPlan {
 size_t plan_backward(const Dims& D, int L, int R, void* ws, BwdPlan& P) {
   Carver cv(ws);
   const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es, Tf1 = (size_t)D.T * D.f1 * D.es;
-  P.saved.assign(D.apps, Saved{});
-  P.xbuf.assign(D.apps, nullptr);
   P.rope = D.rope_geglu ? (float*)cv.take(rope_table_floats(D.S, D.dh) * 4) : nullptr;
   // the right-hand operands of the weight-gradient products are contiguous over the applications
-  char* a_all = (char*)cv.take(D.apps * Td);
-  char* o_all = (char*)cv.take(D.apps * Td);
-  char* c_all = (char*)cv.take(D.apps * Td);
-  char* g_all = (char*)cv.take(D.apps * Tf);
-  for (int i = 0; i < D.apps; ++i) {
-    Saved& s = P.saved[i];
-    s.a = a_all ? a_all + i * Td : nullptr; s.o = o_all ? o_all + i * Td : nullptr;
-    s.c = c_all ? c_all + i * Td : nullptr; s.g = g_all ? g_all + i * Tf : nullptr;
-    s.qkv = cv.take(3 * Td); s.h = cv.take(Td); s.u = cv.take(Tf1);
-    s.mean1 = (float*)cv.take((size_t)D.T * 4); s.rstd1 = (float*)cv.take((size_t)D.T * 4);
-    s.mean2 = (float*)cv.take((size_t)D.T * 4); s.rstd2 = (float*)cv.take((size_t)D.T * 4);
-    s.lse = (float*)cv.take((size_t)D.B * D.H * D.S * 4);
-    s.rope = P.rope;
-    if (i > 0) P.xbuf[i] = cv.take(Td);
+  P.a_all = (char*)cv.take(D.apps * Td);
+  P.o_all = (char*)cv.take(D.apps * Td);
+  P.c_all = (char*)cv.take(D.apps * Td);
+  P.g_all = (char*)cv.take(D.apps * Tf);
+  {
+    Carver slot(nullptr);   // one application's private tensors, measured once; every slot has the same layout
+    slot.take(3 * Td);
+    slot.take(Td); P.off_h = slot.off - Td;
+    slot.take(Tf1); P.off_u = slot.off - Tf1;
+    const size_t stat = ((size_t)D.T * 4 + 255) & ~(size_t)255;   // mean1, rstd1, mean2, rstd2: 256-byte aligned each
+    slot.take(4 * stat); P.off_stats = slot.off - 4 * stat;
+    slot.take((size_t)D.B * D.H * D.S * 4); P.off_lse = slot.off - (size_t)D.B * D.H * D.S * 4;
+    slot.take(Td); P.off_x = slot.off - Td;
+    P.app_pitch = slot.total();
   }
+  P.app_slots = (char*)cv.take(D.apps * P.app_pitch);
   P.du_slots = (char*)cv.take(R * Tf1); P.dh_slots = (char*)cv.take(R * Td); P.dqkv_slots = (char*)cv.take(R * 3 * Td);
   P.dys[0] = D.apps > 1 ? (char*)cv.take(R * Td) : nullptr;
   P.dys[1] = L > 1 ? (char*)cv.take(R * Td) : nullptr;
@@ -339,13 +341,31 @@ size_t plan_backward(const Dims& D, int L, int R, void* ws, BwdPlan& P) {
   return cv.total();
 }
 
+// Where application i keeps the input it was given by application i - 1 (i >= 1).
+void* input_buffer_at(const BwdPlan& P, int i) { return P.app_slots + (size_t)i * P.app_pitch + P.off_x; }
+
+// Intermediates of application i; `x` = its input.
+Saved saved_at(const BwdPlan& P, const Dims& D, int i, const void* x) {
+  const size_t Td = (size_t)D.T * D.d * D.es, Tf = (size_t)D.T * D.f * D.es;
+  char* slot = P.app_slots + (size_t)i * P.app_pitch;
+  Saved s{};
+  s.x = x;
+  s.a = P.a_all + i * Td; s.o = P.o_all + i * Td; s.c = P.c_all + i * Td; s.g = P.g_all + i * Tf;
+  s.qkv = slot; s.h = slot + P.off_h; s.u = slot + P.off_u;
+  float* stats = (float*)(slot + P.off_stats);
+  const size_t stat = (((size_t)D.T * 4 + 255) & ~(size_t)255) / 4;
+  s.mean1 = stats; s.rstd1 = stats + stat; s.mean2 = stats + 2 * stat; s.rstd2 = stats + 3 * stat;
+  s.lse = (float*)(slot + P.off_lse);
+  s.rope = P.rope;
+  return s;
+}
+
 // Recompute the forward from the stage input (keeping every application's intermediates), then the reverse
 // sweep.  grad_in == nullptr: the input gradient leaves int8-encoded in gin_codes / gin_scales.
 swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const swarm_block_params* params,
                           const void* x_in, const void* grad_out, void* grad_in, int8_t* gin_codes,
-                          float* gin_scales, const swarm_block_grads* grad_params, const BwdPlan& P_in,
+                          float* gin_scales, const swarm_block_grads* grad_params, const BwdPlan& P,
                           hipStream_t st) {
-  BwdPlan P = P_in;
   const int L = cfg->n_layers, R = cfg->n_repeat;
   const size_t Td = (size_t)D.T * D.d * D.es, Tf1 = (size_t)D.T * D.f1 * D.es;
   if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
@@ -353,13 +373,14 @@ swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const sw
   int app = 0;
   for (int l = 0; l < L; ++l)
     for (int r = 0; r < R; ++r, ++app) {
-      P.saved[app].x = cur;
-      void* y = (app == D.apps - 1) ? nullptr : P.xbuf[app + 1];   // the stage output itself is not needed
-      SWARM_TRY(block_forward(D, params[l], P.saved[app], y, cfg->ln_eps, st));
+      void* y = (app == D.apps - 1) ? nullptr : input_buffer_at(P, app + 1);   // the stage output is not needed
+      SWARM_TRY(block_forward(D, params[l], saved_at(P, D, app, cur), y, cfg->ln_eps, st));
       cur = y;
     }
-  // With sharing, the last application's output gradient joins the slots of its parameter set.
-  const bool direct = R == 1;   // the last set then reads grad_out in place
+  // With sharing, the last application's output gradient joins the slots of its parameter set, so that the set's
+  // weight gradients stay one product over all its applications: one copy of a [T,d] tensor against a second
+  // read-modify-write pass over the set's fp32 gradient matrices.  Without sharing grad_out is read in place.
+  const bool direct = R == 1;
   if (!direct &&
       hipMemcpyAsync(P.dys[(L - 1) & 1] + (size_t)(R - 1) * Td, grad_out, Td, hipMemcpyDeviceToDevice, st) != hipSuccess)
     return SWARM_ERR_LAUNCH;
@@ -371,12 +392,13 @@ swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const sw
       app = l * R + r;
       const void* dy = from_caller ? grad_out : base + (size_t)r * Td;
       const AppGrads ag{P.du_slots + (size_t)r * Tf1, P.dh_slots + (size_t)r * Td, P.dqkv_slots + (size_t)r * 3 * Td};
+      const Saved sv = saved_at(P, D, app, app == 0 ? x_in : input_buffer_at(P, app));
       if (app == 0) {
-        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, ag, dy, grad_in, st,
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], sv, P.t, ag, dy, grad_in, st,
                                  grad_in ? nullptr : gin_codes, grad_in ? nullptr : gin_scales));
       } else {
         void* dx = r > 0 ? base + (size_t)(r - 1) * Td : P.dys[(l - 1) & 1] + (size_t)(R - 1) * Td;
-        SWARM_TRY(block_backward(D, params[l], grad_params[l], P.saved[app], P.t, ag, dy, dx, st));
+        SWARM_TRY(block_backward(D, params[l], grad_params[l], sv, P.t, ag, dy, dx, st));
       }
     }
     for (int r0 = 0; r0 < R; r0 += chunk) {
@@ -384,7 +406,7 @@ swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const sw
       const void* dy = from_caller ? grad_out : base + (size_t)r0 * Td;
       const AppGrads ag{P.du_slots + (size_t)r0 * Tf1, P.dh_slots + (size_t)r0 * Td,
                         P.dqkv_slots + (size_t)r0 * 3 * Td};
-      SWARM_TRY(set_weight_grads(D, grad_params[l], n, dy, ag, P.saved[l * R + r0], P.t.partial, st));
+      SWARM_TRY(set_weight_grads(D, grad_params[l], n, dy, ag, saved_at(P, D, l * R + r0, nullptr), P.t.partial, st));
     }
   }
   return SWARM_OK;

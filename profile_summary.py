@@ -1,10 +1,10 @@
 """Summarise rocprofv3 CSV output of a bench.py run.
 
-    python -m paper_2301_11913_amd.profile_summary stats  <dir>/<prefix>_kernel_stats.csv
-    python -m paper_2301_11913_amd.profile_summary pmc    <fetch>_counter_collection.csv <write>_counter_collection.csv
+    python profile_summary.py stats  <dir>/<prefix>_kernel_stats.csv
+    python profile_summary.py pmc    <fetch>_counter_collection.csv <write>_counter_collection.csv
                                                           [kernel name prefix = gemm_bf16 [largest]]
 
-    python -m paper_2301_11913_amd.profile_summary counters <counter_collection.csv> [more .csv ...]
+    python profile_summary.py counters <counter_collection.csv> [more .csv ...]
 
 `counters` prints, per kernel family (GEMM: per instantiation; others: name up to the template arguments), the sum over all launches of every
 counter found in the given rocprofv3 --pmc runs of bench.py, and each counter as a fraction of SQ_BUSY_CU_CYCLES

@@ -33,6 +33,20 @@ def test_exports_every_declared_symbol(lib):
         assert getattr(lib, s) is not None
 
 
+def test_product_library_has_no_test_hooks(lib):
+    """Single-kernel entry points, the GEMM launch timer and the micro-benchmarks live in libswarm_hooks.so only."""
+    hooks = ("swarm_kernel_gemm", "swarm_kernel_gemm_ws", "swarm_kernel_gemm_stamped", "swarm_kernel_attention_fwd",
+             "swarm_kernel_attention_bwd", "swarm_kernel_quantise_pairs", "swarm_kernel_timing_enable",
+             "swarm_kernel_timing_collect", "swarm_microbench_mfma_rate", "swarm_microbench_lds_read")
+    for s in hooks:
+        assert not hasattr(lib, s), s
+    if not os.path.exists(sw.hooks_lib_path()):
+        pytest.skip("libswarm_hooks.so not built")
+    hl = sw.load_hooks_library()
+    for s in hooks + tuple(sw.EXPORTED_SYMBOLS):
+        assert getattr(hl, s) is not None
+
+
 def test_status_strings(lib):
     assert sw.swarm_status_string(0) == "ok"
     for code in (-1, -2, -3, -4, -5):

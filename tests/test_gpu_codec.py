@@ -159,7 +159,7 @@ def test_shared_reciprocal_division_gives_the_codes_of_the_ieee_division():
     values within 4 ulps of every tie (k + 1/2) scale."""
     import ctypes
     import paper_2301_11913_amd as sw
-    lib = sw.load_library()
+    lib = sw.load_hooks_library()
     lib.swarm_kernel_quantise_pairs.restype = ctypes.c_int
     lib.swarm_kernel_quantise_pairs.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                 ctypes.c_void_p]

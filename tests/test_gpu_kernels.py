@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 def _lib():
     import paper_2301_11913_amd as sw
-    lib = sw.load_library()
+    lib = sw.load_hooks_library()
     lib.swarm_kernel_gemm.restype = C.c_int
     lib.swarm_kernel_gemm.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
                                                       C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
