@@ -141,7 +141,7 @@ swarm_status swarm_codec_decode(const int8_t *codes, const float *scales, size_t
  * moves the scale by at most 2^-8 relative, so the largest element still gets +-127 and every element's round-trip
  * error stays within half a step; a block whose scale rounds to zero (max|x| < 2^-127) is encoded as zeros.
  * scales [ceil(n/block)] uint16, 2-byte aligned; everything else as in swarm_codec_encode / swarm_codec_decode.
- * The fused stage entry points below use fp32 scales only. */
+ * The fused stage entry points below exist for both scale widths. */
 swarm_status swarm_codec_encode_s16(const void *tensor, int32_t dtype, size_t n_elems, int32_t block,
                                     int8_t *codes, uint16_t *scales, void *hip_stream);
 swarm_status swarm_codec_decode_s16(const int8_t *codes, const uint16_t *scales, size_t n_elems, int32_t block,
@@ -167,6 +167,19 @@ swarm_status swarm_stage_backward_coded(const swarm_stage_config *cfg, const swa
                                         int8_t *gin_codes, float *gin_scales,
                                         const swarm_block_grads *grad_params,
                                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The two fused calls with 16-bit block scales on all four boundary tensors: bit-identical to
+ * swarm_codec_decode_s16 -> swarm_stage_forward / swarm_stage_backward -> swarm_codec_encode_s16.  scales are
+ * uint16 [B*S*d/64] (bf16 bit patterns, 2-byte aligned); everything else as above, same workspace. */
+swarm_status swarm_stage_forward_coded_s16(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                           const int8_t *x_codes, const uint16_t *x_scales, void *x_dec,
+                                           int8_t *y_codes, uint16_t *y_scales,
+                                           void *workspace, size_t workspace_bytes, void *hip_stream);
+swarm_status swarm_stage_backward_coded_s16(const swarm_stage_config *cfg, const swarm_block_params *params,
+                                            const void *x_in, const int8_t *g_codes, const uint16_t *g_scales,
+                                            int8_t *gin_codes, uint16_t *gin_scales,
+                                            const swarm_block_grads *grad_params,
+                                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char *swarm_status_string(swarm_status status);

@@ -20,7 +20,8 @@ EXPORTED_SYMBOLS = ("swarm_stage_workspace_bytes", "swarm_stage_forward", "swarm
                     "swarm_embedding_forward", "swarm_embedding_backward", "swarm_head_workspace_bytes",
                     "swarm_head_loss", "swarm_head_loss_backward",
                     "swarm_lamb_workspace_bytes", "swarm_lamb_step", "swarm_lamb_step_static",
-                    "swarm_codec_encode_s16", "swarm_codec_decode_s16")
+                    "swarm_codec_encode_s16", "swarm_codec_decode_s16",
+                    "swarm_stage_forward_coded_s16", "swarm_stage_backward_coded_s16")
 SWARM_COMPRESS_BOTTLENECK, SWARM_COMPRESS_MAXOUT = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -178,6 +179,11 @@ def _open(path):
     lib.swarm_stage_backward_coded.restype = C.c_int
     lib.swarm_stage_backward_coded.argtypes = [C.POINTER(_Config), C.POINTER(_BlockPtrs)] + [C.c_void_p] * 5 + \
                                               [C.POINTER(_BlockPtrs), C.c_void_p, C.c_size_t, C.c_void_p]
+    for suffix in ("", "_s16"):
+        getattr(lib, "swarm_stage_forward_coded" + suffix).restype = C.c_int
+        getattr(lib, "swarm_stage_forward_coded" + suffix).argtypes = lib.swarm_stage_forward_coded.argtypes
+        getattr(lib, "swarm_stage_backward_coded" + suffix).restype = C.c_int
+        getattr(lib, "swarm_stage_backward_coded" + suffix).argtypes = lib.swarm_stage_backward_coded.argtypes
     lib.swarm_boundary_workspace_bytes.restype = C.c_size_t
     lib.swarm_boundary_workspace_bytes.argtypes = [C.POINTER(_BoundaryConfig), C.c_int, C.c_int]
     for name in ("swarm_compress_forward", "swarm_decompress_forward"):
@@ -327,26 +333,39 @@ def swarm_stage_coded_workspace_bytes(cfg: StageConfig, for_backward: bool) -> i
     return int(load_library().swarm_stage_coded_workspace_bytes(C.byref(cfg.c), 1 if for_backward else 0))
 
 
+def _scale_suffix(*scales: torch.Tensor) -> str:
+    """"" for fp32 block scales, "_s16" for 16-bit ones (all scale tensors of a call must agree)."""
+    sizes = {t.element_size() for t in scales}
+    if sizes == {4} and all(t.dtype == torch.float32 for t in scales):
+        return ""
+    if sizes == {2}:
+        return "_s16"
+    raise TypeError("block scales must be all fp32 or all 16-bit tensors")
+
+
 def swarm_stage_forward_coded(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_codes: torch.Tensor,
                               x_scales: torch.Tensor, x_dec: torch.Tensor, y_codes: torch.Tensor,
                               y_scales: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
-    st = load_library().swarm_stage_forward_coded(C.byref(cfg.c), _block_array(params), _ptr(x_codes), _ptr(x_scales),
-                                                  _ptr(x_dec), _ptr(y_codes), _ptr(y_scales), _ptr(workspace),
-                                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    """fp32 scale tensors call swarm_stage_forward_coded, 16-bit ones swarm_stage_forward_coded_s16."""
+    name = "swarm_stage_forward_coded" + _scale_suffix(x_scales, y_scales)
+    st = getattr(load_library(), name)(C.byref(cfg.c), _block_array(params), _ptr(x_codes), _ptr(x_scales),
+                                       _ptr(x_dec), _ptr(y_codes), _ptr(y_scales), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
-        raise SwarmError(st, "swarm_stage_forward_coded")
+        raise SwarmError(st, name)
 
 
 def swarm_stage_backward_coded(cfg: StageConfig, params: List[Dict[str, torch.Tensor]], x_in: torch.Tensor,
                                g_codes: torch.Tensor, g_scales: torch.Tensor, gin_codes: torch.Tensor,
                                gin_scales: torch.Tensor, grad_params: List[Dict[str, torch.Tensor]],
                                workspace: torch.Tensor, stream=None) -> None:
-    st = load_library().swarm_stage_backward_coded(C.byref(cfg.c), _block_array(params), _ptr(x_in), _ptr(g_codes),
-                                                   _ptr(g_scales), _ptr(gin_codes), _ptr(gin_scales),
-                                                   _block_array(grad_params), _ptr(workspace),
-                                                   workspace.numel() * workspace.element_size(), _stream(stream))
+    name = "swarm_stage_backward_coded" + _scale_suffix(g_scales, gin_scales)
+    st = getattr(load_library(), name)(C.byref(cfg.c), _block_array(params), _ptr(x_in), _ptr(g_codes),
+                                       _ptr(g_scales), _ptr(gin_codes), _ptr(gin_scales),
+                                       _block_array(grad_params), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream))
     if st != 0:
-        raise SwarmError(st, "swarm_stage_backward_coded")
+        raise SwarmError(st, name)
 
 
 def _ptrs3(d: Dict[str, torch.Tensor], wkey: str):

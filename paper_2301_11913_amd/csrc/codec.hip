@@ -151,29 +151,35 @@ static int codec_grid(size_t n_elems) {
   return (int)(blocks < cap ? (blocks ? blocks : 1) : cap);
 }
 
-swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, float* scales, bool bf16,
-                                 hipStream_t st) {
+swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, void* scales, bool bf16,
+                                 hipStream_t st, bool scales16) {
   if (n == 0) return SWARM_OK;
   const int grid = codec_grid(n);
-  if (bf16)
-    hipLaunchKernelGGL(codec_encode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, (const bf16_raw*)tensor, n,
-                       codes, scales);
+  const dim3 g(grid), b(kThreads);
+  if (bf16 && !scales16)
+    hipLaunchKernelGGL((codec_encode_kernel<bf16_raw, float>), g, b, 0, st, (const bf16_raw*)tensor, n, codes, (float*)scales);
+  else if (bf16)
+    hipLaunchKernelGGL((codec_encode_kernel<bf16_raw, uint16_t>), g, b, 0, st, (const bf16_raw*)tensor, n, codes, (uint16_t*)scales);
+  else if (!scales16)
+    hipLaunchKernelGGL((codec_encode_kernel<float, float>), g, b, 0, st, (const float*)tensor, n, codes, (float*)scales);
   else
-    hipLaunchKernelGGL(codec_encode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, (const float*)tensor, n, codes,
-                       scales);
+    hipLaunchKernelGGL((codec_encode_kernel<float, uint16_t>), g, b, 0, st, (const float*)tensor, n, codes, (uint16_t*)scales);
   return launch_status();
 }
 
-swarm_status codec_decode_launch(const int8_t* codes, const float* scales, size_t n, void* tensor, bool bf16,
-                                 hipStream_t st) {
+swarm_status codec_decode_launch(const int8_t* codes, const void* scales, size_t n, void* tensor, bool bf16,
+                                 hipStream_t st, bool scales16) {
   if (n == 0) return SWARM_OK;
   const int grid = codec_grid(n);
-  if (bf16)
-    hipLaunchKernelGGL(codec_decode_kernel<bf16_raw>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n,
-                       (bf16_raw*)tensor);
+  const dim3 g(grid), b(kThreads);
+  if (bf16 && !scales16)
+    hipLaunchKernelGGL((codec_decode_kernel<bf16_raw, float>), g, b, 0, st, codes, (const float*)scales, n, (bf16_raw*)tensor);
+  else if (bf16)
+    hipLaunchKernelGGL((codec_decode_kernel<bf16_raw, uint16_t>), g, b, 0, st, codes, (const uint16_t*)scales, n, (bf16_raw*)tensor);
+  else if (!scales16)
+    hipLaunchKernelGGL((codec_decode_kernel<float, float>), g, b, 0, st, codes, (const float*)scales, n, (float*)tensor);
   else
-    hipLaunchKernelGGL(codec_decode_kernel<float>, dim3(grid), dim3(kThreads), 0, st, codes, scales, n,
-                       (float*)tensor);
+    hipLaunchKernelGGL((codec_decode_kernel<float, uint16_t>), g, b, 0, st, codes, (const uint16_t*)scales, n, (float*)tensor);
   return launch_status();
 }
 
@@ -208,15 +214,7 @@ extern "C" swarm_status swarm_codec_encode_s16(const void* tensor, int32_t dtype
   if (n_elems == 0) return SWARM_OK;
   if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
   if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 1)) return SWARM_ERR_SHAPE;
-  const int grid = codec_grid(n_elems);
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (dtype == SWARM_BF16)
-    hipLaunchKernelGGL((codec_encode_kernel<bf16_raw, uint16_t>), dim3(grid), dim3(kThreads), 0, st,
-                       (const bf16_raw*)tensor, n_elems, codes, scales);
-  else
-    hipLaunchKernelGGL((codec_encode_kernel<float, uint16_t>), dim3(grid), dim3(kThreads), 0, st, (const float*)tensor,
-                       n_elems, codes, scales);
-  return launch_status();
+  return codec_encode_launch(tensor, n_elems, codes, scales, dtype == SWARM_BF16, (hipStream_t)hip_stream, true);
 }
 
 extern "C" swarm_status swarm_codec_decode_s16(const int8_t* codes, const uint16_t* scales, size_t n_elems,
@@ -226,13 +224,5 @@ extern "C" swarm_status swarm_codec_decode_s16(const int8_t* codes, const uint16
   if (n_elems == 0) return SWARM_OK;
   if (!tensor || !codes || !scales) return SWARM_ERR_NULL;
   if (((uintptr_t)tensor & 15) || ((uintptr_t)codes & 7) || ((uintptr_t)scales & 1)) return SWARM_ERR_SHAPE;
-  const int grid = codec_grid(n_elems);
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (dtype == SWARM_BF16)
-    hipLaunchKernelGGL((codec_decode_kernel<bf16_raw, uint16_t>), dim3(grid), dim3(kThreads), 0, st, codes, scales,
-                       n_elems, (bf16_raw*)tensor);
-  else
-    hipLaunchKernelGGL((codec_decode_kernel<float, uint16_t>), dim3(grid), dim3(kThreads), 0, st, codes, scales,
-                       n_elems, (float*)tensor);
-  return launch_status();
+  return codec_decode_launch(codes, scales, n_elems, tensor, dtype == SWARM_BF16, (hipStream_t)hip_stream, true);
 }

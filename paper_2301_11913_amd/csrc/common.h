@@ -72,6 +72,20 @@ struct BlockDivisor {
   }
 };
 
+// Block scale of the boundary codec as stored: fp32, or (s16) its bf16 rounding as a 16-bit pattern.  The codes
+// always divide by the value that is stored, so the encoder rounds the scale BEFORE it quantises.
+__device__ __forceinline__ float block_scale_rounded(float s, bool s16) {
+  return s16 ? __uint_as_float(float_to_bf16_bits(s) << 16) : s;
+}
+__device__ __forceinline__ void block_scale_store(void* scales, size_t i, float s, bool s16) {
+  if (s16) reinterpret_cast<uint16_t*>(scales)[i] = (uint16_t)(__float_as_uint(s) >> 16);
+  else reinterpret_cast<float*>(scales)[i] = s;
+}
+__device__ __forceinline__ float block_scale_load(const void* scales, size_t i, bool s16) {
+  return s16 ? __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(scales)[i] << 16)
+             : reinterpret_cast<const float*>(scales)[i];
+}
+
 inline swarm_status launch_status() {
   return hipGetLastError() == hipSuccess ? SWARM_OK : SWARM_ERR_LAUNCH;
 }

@@ -129,7 +129,8 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
                                                             float* __restrict__ mean, float* __restrict__ rstd,
                                                             int rows, int d, float eps,
                                                             const int8_t* __restrict__ codes,
-                                                            const float* __restrict__ scales, T* __restrict__ xdec) {
+                                                            const void* __restrict__ scales, T* __restrict__ xdec,
+                                                            bool scales16) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nchunk = d >> 3;
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
         if constexpr (DEC) {
           const size_t e0 = (size_t)row * d + (size_t)c * 8;
           const uint2 cw = *reinterpret_cast<const uint2*>(codes + e0);
-          const float sc = scales[e0 >> 6];
+          const float sc = block_scale_load(scales, e0 >> 6, scales16);
           const uint32_t w[2] = {cw.x, cw.y};
           float t[8];
 #pragma unroll
@@ -244,8 +245,9 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
                                                             const T* __restrict__ gamma, const T* __restrict__ dres,
                                                             T* __restrict__ dx, float* __restrict__ partial, int rows,
                                                             int d, int8_t* __restrict__ codes,
-                                                            float* __restrict__ scales, int rpb,
-                                                            const T* __restrict__ beta = nullptr) {
+                                                            void* __restrict__ scales, int rpb,
+                                                            const T* __restrict__ beta = nullptr,
+                                                            bool scales16 = false) {
   __shared__ float red[2][kLnBatch][kLnWaves][2];
   typedef typename V8<T>::Raw Raw;
   const int lane = threadIdx.x & 63;
@@ -337,7 +339,13 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
           V8<T>::unpack(dyraw[r][it], dv);
           V8<T>::unpack(graw[it], g);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) o[i] = res[i] + rs[r] * (dv[i] * g[i] - m1 - (xv[i] - mu[r]) * rs[r] * m2);
+          for (int i = 0; i < 8; ++i) {
+            // written out operation by operation: the storing and the int8-encoding instantiation must round
+            // the same fp32 value, whatever the optimiser would make of an expression
+            const float xh = (xv[i] - mu[r]) * rs[r];
+            const float t = __builtin_fmaf(-xh, m2, dv[i] * g[i] - m1);
+            o[i] = __builtin_fmaf(rs[r], t, res[i]);
+          }
           if constexpr (ENC) {
             const size_t e0 = (size_t)row * d + (size_t)(cbase + c) * 8;
             float amax = 0.f;
@@ -346,7 +354,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
             amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
             amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
             amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
-            const float sc = amax / 127.0f;
+            const float sc = block_scale_rounded(amax / 127.0f, scales16);
             uint32_t w[2] = {0u, 0u};
             if (sc != 0.0f) {
               const BlockDivisor div(sc);
@@ -357,7 +365,7 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
               }
             }
             *reinterpret_cast<uint2*>(codes + e0) = make_uint2(w[0], w[1]);
-            if ((lane & 7) == 0) scales[e0 >> 6] = sc;
+            if ((lane & 7) == 0) block_scale_store(scales, e0 >> 6, sc, scales16);
           } else {
             V8<T>::store(dx + (size_t)row * d + (size_t)(cbase + c) * 8, o);
           }
@@ -442,11 +450,12 @@ __global__ __launch_bounds__(256) void reduce_rows_accum_kernel(const float* __r
 
 template <typename T, bool DEC, int MAXK = 0>
 swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows, int d,
-                             float eps, const int8_t* codes, const float* scales, T* xdec, hipStream_t st) {
+                             float eps, const int8_t* codes, const void* scales, T* xdec, hipStream_t st,
+                             bool scales16 = false) {
   const int grid = std::min((rows + kLnWaves - 1) / kLnWaves, 256 * 8);
 #define LN_FWD(NIT)                                                                                           \
   hipLaunchKernelGGL((ln_fwd_kernel<T, NIT, DEC, MAXK>), dim3(grid), dim3(kLnThreads), 0, st, x, g, b, y, mean, \
-                     rstd, rows, d, eps, codes, scales, xdec)
+                     rstd, rows, d, eps, codes, scales, xdec, scales16)
   if (d <= 512) LN_FWD(1);
   else if (d <= 1024) LN_FWD(2);
   else if (d <= 2048) LN_FWD(4);
@@ -459,13 +468,13 @@ swarm_status ln_fwd_dispatch(const T* x, const T* g, const T* b, T* y, float* me
 
 template <typename T, bool ENC, int MAXK = 0>
 swarm_status ln_bwd_dispatch(const T* dy, const T* x, const float* mean, const float* rstd, const T* g,
-                             const T* dres, T* dx, float* partial, int rows, int d, int8_t* codes, float* scales,
-                             hipStream_t st, const T* beta = nullptr) {
+                             const T* dres, T* dx, float* partial, int rows, int d, int8_t* codes, void* scales,
+                             hipStream_t st, const T* beta = nullptr, bool scales16 = false) {
   const int rpb = ln_rows_per_block(rows);
   const int grid = (rows + rpb - 1) / rpb;
 #define LN_BWD(NITQ)                                                                                                \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NITQ, ENC, MAXK>), dim3(grid), dim3(kLnThreads), 0, st, dy, x, mean, rstd, g, \
-                     dres, dx, partial, rows, d, codes, scales, rpb, beta)
+                     dres, dx, partial, rows, d, codes, scales, rpb, beta, scales16)
   if (d <= 2048) LN_BWD(1);
   else if (d <= 4096) LN_BWD(2);
   else if (d <= 8192) LN_BWD(4);
@@ -485,14 +494,14 @@ swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, v
                                        rstd, T, d, eps, nullptr, nullptr, nullptr, st);
 }
 
-swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void* xdec, const void* gamma,
+swarm_status layernorm_fwd_decode(const int8_t* codes, const void* scales, void* xdec, const void* gamma,
                                   const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
-                                  bool bf16, hipStream_t st) {
+                                  bool bf16, hipStream_t st, bool scales16) {
   if (bf16)
     return ln_fwd_dispatch<bf16_raw, true>(nullptr, (const bf16_raw*)gamma, (const bf16_raw*)beta, (bf16_raw*)y,
-                                           mean, rstd, T, d, eps, codes, scales, (bf16_raw*)xdec, st);
+                                           mean, rstd, T, d, eps, codes, scales, (bf16_raw*)xdec, st, scales16);
   return ln_fwd_dispatch<float, true>(nullptr, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, T, d,
-                                      eps, codes, scales, (float*)xdec, st);
+                                      eps, codes, scales, (float*)xdec, st, scales16);
 }
 
 size_t layernorm_bwd_scratch_floats(int T, int d) {
@@ -503,18 +512,20 @@ size_t layernorm_bwd_scratch_floats(int T, int d) {
 // codes != nullptr: dx is not written; its int8 encoding goes to codes / scales (needs d % 256 == 0)
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
-                           bool bf16, hipStream_t st, int8_t* codes, float* scales) {
+                           bool bf16, hipStream_t st, int8_t* codes, void* scales, bool scales16) {
   swarm_status s;
   if (codes && (d % 256)) return SWARM_ERR_SHAPE;
   if (bf16) {
     const bf16_raw *a = (const bf16_raw*)dy, *b = (const bf16_raw*)x, *g = (const bf16_raw*)gamma,
                    *r = (const bf16_raw*)dres;
-    s = codes ? ln_bwd_dispatch<bf16_raw, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st)
+    s = codes ? ln_bwd_dispatch<bf16_raw, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st,
+                                                nullptr, scales16)
               : ln_bwd_dispatch<bf16_raw, false>(a, b, mean, rstd, g, r, (bf16_raw*)dx, partial, T, d, nullptr, nullptr,
                                                  st);
   } else {
     const float *a = (const float*)dy, *b = (const float*)x, *g = (const float*)gamma, *r = (const float*)dres;
-    s = codes ? ln_bwd_dispatch<float, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st)
+    s = codes ? ln_bwd_dispatch<float, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st, nullptr,
+                                             scales16)
               : ln_bwd_dispatch<float, false>(a, b, mean, rstd, g, r, (float*)dx, partial, T, d, nullptr, nullptr, st);
   }
   if (s != SWARM_OK) return s;

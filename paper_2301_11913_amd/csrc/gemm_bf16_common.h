@@ -18,7 +18,7 @@ struct KArgs {
   int epilogue;
   const bf16_raw* bias; const bf16_raw* aux; int ldaux;
   bf16_raw* C2; int ldc2;
-  float* scales;   // EPI_BIAS_RESID_ENCODE
+  void* scales; int scales16;   // EPI_BIAS_RESID_ENCODE (scales16: bf16 bit patterns instead of fp32)
   const float* rope; int rope_S, rope_dh, rope_cols;   // EPI_BIAS_ROPE
   int split;       // EPI_DGEGLU, EPI_BIAS_GEGLU
   int tiles_m, tiles_n;
@@ -254,7 +254,7 @@ __device__ __forceinline__ void gemm_epilogue_nt(const KArgs& p, const Acc& acc,
         amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
         amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
         amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
-        const float sc = amax / 127.0f;
+        const float sc = block_scale_rounded(amax / 127.0f, p.scales16);
         uint32_t w[2] = {0u, 0u};
         if (sc != 0.0f) {
           const BlockDivisor div(sc);
@@ -266,7 +266,7 @@ __device__ __forceinline__ void gemm_epilogue_nt(const KArgs& p, const Acc& acc,
         }
         const size_t e0 = (size_t)row * p.ldc + col;
         *reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(p.C) + e0) = make_uint2(w[0], w[1]);
-        if (c8 == 0) p.scales[e0 >> 6] = sc;
+        if (c8 == 0) block_scale_store(p.scales, e0 >> 6, sc, p.scales16);
         continue;
       }
       if (epi == EPI_BIAS) {

@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(KArgs p) {
     amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
     amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
     amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
-    const float sc = amax / 127.0f;
+    const float sc = block_scale_rounded(amax / 127.0f, p.scales16);
     uint32_t w[2] = {0u, 0u};
     if (sc != 0.0f) {
       const BlockDivisor div(sc);
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(KArgs p) {
     }
     const size_t e0 = row * p.ldc + col;
     *reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(p.C) + e0) = make_uint2(w[0], w[1]);
-    if ((col & 63) == 0) p.scales[e0 >> 6] = sc;
+    if ((col & 63) == 0) block_scale_store(p.scales, e0 >> 6, sc, p.scales16);
   } else {
     *reinterpret_cast<uint4*>(reinterpret_cast<bf16_raw*>(p.C) + row * p.ldc + col) = pack8_bf16(x);
   }
@@ -617,7 +617,7 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
   k.group_m = 8;   // measured best of {2,4,8,16,32} on the d=4096 shapes
   k.A = (const bf16_raw*)g.A; k.B = (const bf16_raw*)g.B; k.M = g.M; k.N = g.N; k.K = g.K; k.lda = g.lda;
   k.ldb = g.ldb; k.C = g.C; k.ldc = g.ldc; k.epilogue = g.epilogue; k.bias = (const bf16_raw*)g.bias;
-  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales;
+  k.aux = (const bf16_raw*)g.aux; k.ldaux = g.ldaux; k.C2 = (bf16_raw*)g.C2; k.ldc2 = g.ldc2; k.scales = g.scales; k.scales16 = g.scales16;
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
   k.ksplit = 1; k.part = nullptr; k.stamps = g.stamps;
   // An output of at least twice the 32 MB of L2 cannot wait there for its consumer; written (and its residual /

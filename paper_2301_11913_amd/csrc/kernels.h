@@ -38,7 +38,8 @@ struct GemmArgs {
   const void* bias;        // [N], activation dtype
   const void* aux; int ldaux;   // [M,N] residual or pre-activation, activation dtype
   void* C2; int ldc2;      // optional second output (pre-activation u)
-  float* scales;           // EPI_BIAS_RESID_ENCODE: one fp32 scale per 64 consecutive elements of C (ldc == N)
+  void* scales;            // EPI_BIAS_RESID_ENCODE: one scale per 64 consecutive elements of C (ldc == N): fp32, or
+  bool scales16;           // (scales16) bf16 bit patterns, the codes then dividing by the rounded scale
   const float* rope;       // EPI_BIAS_ROPE: (cos, sin) table [rope_S, rope_dh/2]; row m is at position m % rope_S,
   int rope_S, rope_dh, rope_cols;   // a head spans rope_dh columns, columns >= rope_cols are left alone
   int split;               // EPI_DGEGLU / EPI_BIAS_GEGLU: f, the width of the gate (and of the up) half
@@ -66,7 +67,8 @@ size_t layernorm_bwd_scratch_floats(int T, int d);
 // With codes != nullptr dx is not stored: its int8 blockwise encoding is (fused stage-exit encode, d % 256 == 0).
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
-                           bool bf16, hipStream_t st, int8_t* codes = nullptr, float* scales = nullptr);
+                           bool bf16, hipStream_t st, int8_t* codes = nullptr, void* scales = nullptr,
+                           bool scales16 = false);
 // LayerNorm fused with the maxout that follows it in the compression-aware sender (k in {2, 4, 8}; other k:
 // SWARM_ERR_SHAPE and nothing launched): z [T, d/k] = maxout_k(LN(x)), the normalised row is never stored.  The
 // window maximum is taken on the normalised values rounded to the dtype.  k = -1: mean and rstd only.
@@ -78,14 +80,15 @@ swarm_status layernorm_bwd_maxout(const void* dz, const void* x, const float* me
                                   const void* gamma, const void* beta, void* dx, float* dgamma, float* dbeta,
                                   float* partial, int T, int d, int k, bool bf16, hipStream_t st);
 // LayerNorm of a row that arrives int8-encoded: xdec receives the decoded row (fused stage-entry decode).
-swarm_status layernorm_fwd_decode(const int8_t* codes, const float* scales, void* xdec, const void* gamma,
+swarm_status layernorm_fwd_decode(const int8_t* codes, const void* scales, void* xdec, const void* gamma,
                                   const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
-                                  bool bf16, hipStream_t st);
+                                  bool bf16, hipStream_t st, bool scales16 = false);
 // Stand-alone codec launches (same kernels as the C ABI entry points).
-swarm_status codec_decode_launch(const int8_t* codes, const float* scales, size_t n, void* tensor, bool bf16,
-                                 hipStream_t st);
-swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, float* scales, bool bf16,
-                                 hipStream_t st);
+// (scales16: the scales are bf16 bit patterns, as in swarm_codec_encode_s16 / swarm_codec_decode_s16)
+swarm_status codec_decode_launch(const int8_t* codes, const void* scales, size_t n, void* tensor, bool bf16,
+                                 hipStream_t st, bool scales16 = false);
+swarm_status codec_encode_launch(const void* tensor, size_t n, int8_t* codes, void* scales, bool bf16,
+                                 hipStream_t st, bool scales16 = false);
 // out[n] += sum_t X[t,n]  (X [T,N] in the activation dtype, out fp32); scratch of colsum_scratch_floats floats.
 size_t colsum_scratch_floats(int T, int N);
 swarm_status colsum_accum(const void* X, int T, int N, float* out, float* partial, bool bf16, hipStream_t st);

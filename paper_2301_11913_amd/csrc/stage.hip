@@ -106,8 +106,9 @@ swarm_status gemm(const Dims& D, const GemmArgs& g, hipStream_t st) {
 // Stage-boundary codec fused into a block: `in_codes` -> the block input arrives int8-encoded and is decoded
 // into s.x by LN1; `out_codes` -> the block output leaves int8-encoded from the FFN2 epilogue.
 struct Boundary {
-  const int8_t* in_codes = nullptr; const float* in_scales = nullptr;
-  int8_t* out_codes = nullptr; float* out_scales = nullptr;
+  const int8_t* in_codes = nullptr; const void* in_scales = nullptr;
+  int8_t* out_codes = nullptr; void* out_scales = nullptr;
+  bool scales16 = false;   // block scales are bf16 bit patterns instead of fp32
 };
 
 // y = block(x): writes every intermediate into `s`; the last GEMM is skipped when y == nullptr.
@@ -116,7 +117,7 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
   const int T = D.T, d = D.d, f = D.f;
   if (bd.in_codes)
     SWARM_TRY(layernorm_fwd_decode(bd.in_codes, bd.in_scales, const_cast<void*>(s.x), p.ln1_g, p.ln1_b, s.a, s.mean1,
-                                   s.rstd1, T, d, eps, D.bf16, st));
+                                   s.rstd1, T, d, eps, D.bf16, st, bd.scales16));
   else
     SWARM_TRY(layernorm_fwd(s.x, p.ln1_g, p.ln1_b, s.a, s.mean1, s.rstd1, T, d, eps, D.bf16, st));
   GemmArgs q{};
@@ -170,7 +171,9 @@ swarm_status block_forward(const Dims& D, const swarm_block_params& p, const Sav
     GemmArgs f2{};
     f2.M = T; f2.N = d; f2.K = f; f2.A = s.g; f2.lda = f; f2.B = p.w_2; f2.ldb = f; f2.C = y; f2.ldc = d;
     f2.epilogue = EPI_BIAS_RESID; f2.bias = p.b_2; f2.aux = s.h; f2.ldaux = d;
-    if (bd.out_codes) { f2.epilogue = EPI_BIAS_RESID_ENCODE; f2.C = bd.out_codes; f2.scales = bd.out_scales; }
+    if (bd.out_codes) {
+      f2.epilogue = EPI_BIAS_RESID_ENCODE; f2.C = bd.out_codes; f2.scales = bd.out_scales; f2.scales16 = bd.scales16;
+    }
     SWARM_TRY(gemm(D, f2, st));
   }
   return SWARM_OK;
@@ -214,7 +217,7 @@ swarm_status data_grad(const Dims& D, const void* dY, int n_out, const void* W, 
 // left to set_weight_grads, which reads dy and the tensors stored in `ag`.
 swarm_status block_backward(const Dims& D, const swarm_block_params& p, const swarm_block_grads& gp, const Saved& s,
                             const BwdTemps& t, const AppGrads& ag, const void* dy, void* dx, hipStream_t st,
-                            int8_t* dx_codes = nullptr, float* dx_scales = nullptr) {
+                            int8_t* dx_codes = nullptr, void* dx_scales = nullptr, bool scales16 = false) {
   const int d = D.d, f = D.f;
   // y = h + g W2^T + b2,  g = gelu(u)  or  gelu(u_gate) * u_up
   if (D.rope_geglu) {
@@ -249,7 +252,7 @@ swarm_status block_backward(const Dims& D, const swarm_block_params& p, const sw
   SWARM_TRY(data_grad(D, ag.dqkv, 3 * d, p.w_qkv, d, t.da, EPI_STORE, nullptr, st));
   // a = LN1(x);  dx = dh + LN1'(da)
   SWARM_TRY(layernorm_bwd(t.da, s.x, s.mean1, s.rstd1, p.ln1_g, ag.dh, dx, gp.ln1_g, gp.ln1_b, t.partial, D.T, d,
-                          D.bf16, st, dx_codes, dx_scales));
+                          D.bf16, st, dx_codes, dx_scales, scales16));
   return SWARM_OK;
 }
 
@@ -364,8 +367,8 @@ Saved saved_at(const BwdPlan& P, const Dims& D, int i, const void* x) {
 // sweep.  grad_in == nullptr: the input gradient leaves int8-encoded in gin_codes / gin_scales.
 swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const swarm_block_params* params,
                           const void* x_in, const void* grad_out, void* grad_in, int8_t* gin_codes,
-                          float* gin_scales, const swarm_block_grads* grad_params, const BwdPlan& P,
-                          hipStream_t st) {
+                          void* gin_scales, const swarm_block_grads* grad_params, const BwdPlan& P,
+                          hipStream_t st, bool scales16 = false) {
   const int L = cfg->n_layers, R = cfg->n_repeat;
   const size_t Td = (size_t)D.T * D.d * D.es, Tf1 = (size_t)D.T * D.f1 * D.es;
   if (P.rope) SWARM_TRY(rope_table(P.rope, D.S, D.dh, st));
@@ -395,7 +398,7 @@ swarm_status run_backward(const Dims& D, const swarm_stage_config* cfg, const sw
       const Saved sv = saved_at(P, D, app, app == 0 ? x_in : input_buffer_at(P, app));
       if (app == 0) {
         SWARM_TRY(block_backward(D, params[l], grad_params[l], sv, P.t, ag, dy, grad_in, st,
-                                 grad_in ? nullptr : gin_codes, grad_in ? nullptr : gin_scales));
+                                 grad_in ? nullptr : gin_codes, grad_in ? nullptr : gin_scales, scales16));
       } else {
         void* dx = r > 0 ? base + (size_t)(r - 1) * Td : P.dys[(l - 1) & 1] + (size_t)(R - 1) * Td;
         SWARM_TRY(block_backward(D, params[l], grad_params[l], sv, P.t, ag, dy, dx, st));
@@ -501,15 +504,18 @@ extern "C" size_t swarm_stage_coded_workspace_bytes(const swarm_stage_config* cf
   return base + 256 + 2 * (((size_t)D.T * D.d * D.es + 255) & ~(size_t)255);   // two boundary tensors of scratch
 }
 
-extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
-                                                  const int8_t* x_codes, const float* x_scales, void* x_dec,
-                                                  int8_t* y_codes, float* y_scales, void* workspace,
-                                                  size_t workspace_bytes, void* hip_stream) {
+namespace swarm {
+namespace {
+
+swarm_status forward_coded(const swarm_stage_config* cfg, const swarm_block_params* params, const int8_t* x_codes,
+                           const void* x_scales, void* x_dec, int8_t* y_codes, void* y_scales, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, bool scales16) {
   if (!cfg || !params || !x_codes || !x_scales || !x_dec || !y_codes || !y_scales || !workspace) return SWARM_ERR_NULL;
   if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
   if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
   if (!params_ok(params, cfg->n_layers)) return SWARM_ERR_NULL;
-  if (!aligned16(x_dec) || !aligned16(x_codes) || !aligned16(y_codes) || ((uintptr_t)workspace & 255))
+  if (!aligned16(x_dec) || !aligned16(x_codes) || !aligned16(y_codes) || ((uintptr_t)workspace & 255) ||
+      (((uintptr_t)x_scales | (uintptr_t)y_scales) & (scales16 ? 1 : 3)))
     return SWARM_ERR_SHAPE;
   if (swarm_stage_coded_workspace_bytes(cfg, 0) > workspace_bytes) return SWARM_ERR_WORKSPACE;
   Dims D = dims_of(cfg);
@@ -518,9 +524,9 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
   void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
   const size_t n = (size_t)D.T * D.d;
   if (!fuse_codec(D)) {
-    SWARM_TRY(codec_decode_launch(x_codes, x_scales, n, x_dec, D.bf16, st));
+    SWARM_TRY(codec_decode_launch(x_codes, x_scales, n, x_dec, D.bf16, st, scales16));
     SWARM_TRY(swarm_stage_forward(cfg, params, x_dec, tmp, workspace, base, hip_stream));
-    return codec_encode_launch(tmp, n, y_codes, y_scales, D.bf16, st);
+    return codec_encode_launch(tmp, n, y_codes, y_scales, D.bf16, st, scales16);
   }
   FwdPlan P;
   plan_forward(D, workspace, P);
@@ -532,6 +538,7 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
     for (int r = 0; r < cfg->n_repeat; ++r, ++app) {
       const bool last = app == D.apps - 1;
       Boundary bd;
+      bd.scales16 = scales16;
       if (app == 0) { bd.in_codes = x_codes; bd.in_scales = x_scales; }
       if (last) { bd.out_codes = y_codes; bd.out_scales = y_scales; }
       void* y = last ? nullptr : P.z[app & 1];
@@ -542,18 +549,18 @@ extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg,
   return SWARM_OK;
 }
 
-extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
-                                                   const void* x_in, const int8_t* g_codes, const float* g_scales,
-                                                   int8_t* gin_codes, float* gin_scales,
-                                                   const swarm_block_grads* grad_params, void* workspace,
-                                                   size_t workspace_bytes, void* hip_stream) {
+swarm_status backward_coded(const swarm_stage_config* cfg, const swarm_block_params* params, const void* x_in,
+                            const int8_t* g_codes, const void* g_scales, int8_t* gin_codes, void* gin_scales,
+                            const swarm_block_grads* grad_params, void* workspace, size_t workspace_bytes,
+                            void* hip_stream, bool scales16) {
   if (!cfg || !params || !x_in || !g_codes || !g_scales || !gin_codes || !gin_scales || !grad_params || !workspace)
     return SWARM_ERR_NULL;
   if (cfg->dtype != SWARM_F32 && cfg->dtype != SWARM_BF16) return SWARM_ERR_DTYPE;
   if (!valid_config(cfg)) return SWARM_ERR_SHAPE;
   if (!params_ok(params, cfg->n_layers) || !params_ok((const swarm_block_params*)grad_params, cfg->n_layers))
     return SWARM_ERR_NULL;
-  if (!aligned16(x_in) || !aligned16(g_codes) || !aligned16(gin_codes) || ((uintptr_t)workspace & 255))
+  if (!aligned16(x_in) || !aligned16(g_codes) || !aligned16(gin_codes) || ((uintptr_t)workspace & 255) ||
+      (((uintptr_t)g_scales | (uintptr_t)gin_scales) & (scales16 ? 1 : 3)))
     return SWARM_ERR_SHAPE;
   if (swarm_stage_coded_workspace_bytes(cfg, 1) > workspace_bytes) return SWARM_ERR_WORKSPACE;
   Dims D = dims_of(cfg);
@@ -562,14 +569,51 @@ extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg
   void* tmp = (char*)workspace + ((base + 255) & ~(size_t)255);
   const size_t n = (size_t)D.T * D.d;
   // the output gradient has several readers (bias sums, two GEMMs, LayerNorm backward): decode it once
-  SWARM_TRY(codec_decode_launch(g_codes, g_scales, n, tmp, D.bf16, st));
+  SWARM_TRY(codec_decode_launch(g_codes, g_scales, n, tmp, D.bf16, st, scales16));
   if (!fuse_codec(D)) {
     void* gin = (char*)tmp + (((size_t)D.T * D.d * D.es + 255) & ~(size_t)255);
     SWARM_TRY(swarm_stage_backward(cfg, params, x_in, tmp, gin, grad_params, workspace, base, hip_stream));
-    return codec_encode_launch(gin, n, gin_codes, gin_scales, D.bf16, st);
+    return codec_encode_launch(gin, n, gin_codes, gin_scales, D.bf16, st, scales16);
   }
   BwdPlan P;
   plan_backward(D, cfg->n_layers, cfg->n_repeat, workspace, P);
   D.splitk = P.splitk; D.splitk_floats = P.splitk ? splitk_floats_of(D) : 0;
-  return run_backward(D, cfg, params, x_in, tmp, nullptr, gin_codes, gin_scales, grad_params, P, st);
+  return run_backward(D, cfg, params, x_in, tmp, nullptr, gin_codes, gin_scales, grad_params, P, st, scales16);
+}
+
+}  // namespace
+}  // namespace swarm
+
+extern "C" swarm_status swarm_stage_forward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                  const int8_t* x_codes, const float* x_scales, void* x_dec,
+                                                  int8_t* y_codes, float* y_scales, void* workspace,
+                                                  size_t workspace_bytes, void* hip_stream) {
+  return forward_coded(cfg, params, x_codes, x_scales, x_dec, y_codes, y_scales, workspace, workspace_bytes,
+                       hip_stream, false);
+}
+
+extern "C" swarm_status swarm_stage_backward_coded(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                   const void* x_in, const int8_t* g_codes, const float* g_scales,
+                                                   int8_t* gin_codes, float* gin_scales,
+                                                   const swarm_block_grads* grad_params, void* workspace,
+                                                   size_t workspace_bytes, void* hip_stream) {
+  return backward_coded(cfg, params, x_in, g_codes, g_scales, gin_codes, gin_scales, grad_params, workspace,
+                        workspace_bytes, hip_stream, false);
+}
+
+extern "C" swarm_status swarm_stage_forward_coded_s16(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                      const int8_t* x_codes, const uint16_t* x_scales, void* x_dec,
+                                                      int8_t* y_codes, uint16_t* y_scales, void* workspace,
+                                                      size_t workspace_bytes, void* hip_stream) {
+  return forward_coded(cfg, params, x_codes, x_scales, x_dec, y_codes, y_scales, workspace, workspace_bytes,
+                       hip_stream, true);
+}
+
+extern "C" swarm_status swarm_stage_backward_coded_s16(const swarm_stage_config* cfg, const swarm_block_params* params,
+                                                       const void* x_in, const int8_t* g_codes,
+                                                       const uint16_t* g_scales, int8_t* gin_codes,
+                                                       uint16_t* gin_scales, const swarm_block_grads* grad_params,
+                                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return backward_coded(cfg, params, x_in, g_codes, g_scales, gin_codes, gin_scales, grad_params, workspace,
+                        workspace_bytes, hip_stream, true);
 }

@@ -10,33 +10,40 @@ from oracle import codec as ocodec, stage as osg
 pytestmark = pytest.mark.gpu
 
 
-def _run(wl, seed_shift=0):
+def _run(wl, scale_bits=32):
+    """Fused entry points against decode -> stage -> encode on the GPU, bit for bit, with fp32 (32) or 16-bit block
+    scales on all four boundary tensors.  Returns the parameters and the oracle's / the GPU's codes and scales."""
     import paper_2301_11913_amd as sw
+    s16 = scale_bits == 16
+    enc = sw.swarm_codec_encode_s16 if s16 else sw.swarm_codec_encode
+    dec = sw.swarm_codec_decode_s16 if s16 else sw.swarm_codec_decode
     params = synth.make_params(wl)
     x, G = synth.make_x_in(wl), synth.make_grad_out(wl)
     bf = wl.dtype == "bf16"
     dt = torch.bfloat16 if bf else torch.float32
     dev = lambda a: (torch.from_numpy(np.ascontiguousarray(a)).to(dt)).cuda()
-    cx, sx = ocodec.encode(x.reshape(-1))
-    cg, sg = ocodec.encode(G.reshape(-1))
+    cx, sx = ocodec.encode(x.reshape(-1), scale_bits=scale_bits)
+    cg, sg = ocodec.encode(G.reshape(-1), scale_bits=scale_bits)
+    if s16:
+        sx, sg = sx.view(np.int16), sg.view(np.int16)              # bf16 bit patterns in a 16-bit torch tensor
     cfg = sw.StageConfig(wl.d_model, wl.n_heads, wl.d_ffn, wl.n_layers, wl.n_repeat, wl.batch, wl.seq, wl.dtype,
                          block_kind=wl.block)
     dp = [{k: dev(p[k]) for k in sw.PARAM_FIELDS} for p in params]
     n = x.size
     i8 = lambda: torch.full((n,), 55, dtype=torch.int8, device="cuda")
-    f32 = lambda: torch.full((n // 64,), -3.0, dtype=torch.float32, device="cuda")
+    f32 = lambda: torch.full((n // 64,), -3, dtype=torch.int16 if s16 else torch.float32, device="cuda")
     cxd, sxd, cgd, sgd = (torch.from_numpy(a).cuda() for a in (cx, sx, cg, sg))
 
     # --- unfused reference path on the GPU
     xd = torch.empty(x.shape, dtype=dt, device="cuda"); gd = torch.empty_like(xd)
-    sw.swarm_codec_decode(cxd, sxd, xd); sw.swarm_codec_decode(cgd, sgd, gd)
+    dec(cxd, sxd, xd); dec(cgd, sgd, gd)
     ws = torch.empty(sw.swarm_stage_workspace_bytes(cfg, True), dtype=torch.uint8, device="cuda")
     y = torch.empty_like(xd); gin = torch.empty_like(xd)
     gp = [{k: torch.zeros(p[k].shape, dtype=torch.float32, device="cuda") for k in sw.PARAM_FIELDS} for p in params]
     sw.swarm_stage_forward(cfg, dp, xd, y, ws)
     sw.swarm_stage_backward(cfg, dp, xd, gd, gin, gp, ws)
     cy, sy, cgi, sgi = i8(), f32(), i8(), f32()
-    sw.swarm_codec_encode(y, cy, sy); sw.swarm_codec_encode(gin, cgi, sgi)
+    enc(y, cy, sy); enc(gin, cgi, sgi)
 
     # --- fused path
     ws2 = torch.empty(max(sw.swarm_stage_coded_workspace_bytes(cfg, True), sw.swarm_stage_coded_workspace_bytes(cfg, False)),
@@ -53,7 +60,9 @@ def _run(wl, seed_shift=0):
     for a, b in zip(gp, gp2):
         for k in a:
             assert torch.equal(a[k], b[k]), k
-    return params, cx, sx, cg, sg, cy2.cpu().numpy(), sy2.cpu().numpy(), cgi2.cpu().numpy(), sgi2.cpu().numpy()
+    u16 = lambda a: a.view(np.uint16) if s16 else a
+    return params, cx, u16(sx), cg, u16(sg), cy2.cpu().numpy(), u16(sy2.cpu().numpy()), cgi2.cpu().numpy(), \
+        u16(sgi2.cpu().numpy())
 
 
 @pytest.mark.parametrize("shape", [
@@ -64,19 +73,22 @@ def _run(wl, seed_shift=0):
     ("bf16", 128, 2, 192, 37, 3, 1, 1),
     ("f32", 256, 4, 1024, 64, 2, 1, 1),
 ])
-def test_coded_equals_unfused(shape):
+@pytest.mark.parametrize("scale_bits", [32, 16])
+def test_coded_equals_unfused(shape, scale_bits):
     dtype, d, H, f, S, B, L, R = shape
     wl = synth.Workload(name="coded", dtype=dtype, d_model=d, n_heads=H, d_ffn=f, seq=S, batch=B, n_layers=L,
                         n_repeat=R, grad_sigma=1.0 if dtype == "f32" else 1e-2, seed=911 + d + S)
-    _run(wl)
+    _run(wl, scale_bits)
 
 
-def test_coded_against_oracle_chain():
-    """decode (oracle) -> oracle stage -> compare decoded GPU outputs within the bf16 tolerance plus one
-    quantisation step of the output codec."""
+@pytest.mark.parametrize("scale_bits", [32, 16])
+def test_coded_against_oracle_chain(scale_bits):
+    """decode (oracle) -> oracle stage -> compare decoded GPU outputs within the bf16 tolerance plus half a
+    quantisation step of the output codec; the GPU's codes and scales are also the oracle codec's on the GPU's
+    own decoded values (re-encoding what was decoded gives the same codes)."""
     wl = synth.Workload(name="coded", dtype="bf16", d_model=256, n_heads=2, d_ffn=512, seq=96, batch=2,
                         n_layers=1, n_repeat=2, grad_sigma=1e-2, seed=3)
-    params, cx, sx, cg, sg, cy, sy, cgi, sgi = _run(wl)
+    params, cx, sx, cg, sg, cy, sy, cgi, sgi = _run(wl, scale_bits)
     shape = (wl.batch, wl.seq, wl.d_model)
     x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(shape)
     G = ocodec.bf16_bits_to_f32(ocodec.decode(cg, sg, out="bf16")).reshape(shape)
@@ -84,5 +96,8 @@ def test_coded_against_oracle_chain():
     rgin = osg.stage_backward(params, x, G, osg.zero_grads(params), wl.n_heads, wl.n_repeat)
     for codes, scales, ref in ((cy, sy, ry), (cgi, sgi, rgin)):
         got = ocodec.decode(codes, scales).reshape(shape).astype(np.float64)
-        step = np.repeat(scales.astype(np.float64), 64).reshape(shape)
+        sc = ocodec.bf16_bits_to_f32(scales) if scale_bits == 16 else scales
+        step = np.repeat(sc.astype(np.float64), 64).reshape(shape)
         assert np.all(np.abs(got - ref) <= 2e-2 * np.max(np.abs(ref)) + 0.5 * step + 1e-12)
+        rc, _ = ocodec.encode(ocodec.decode(codes, scales), scale_bits=scale_bits)
+        assert np.array_equal(rc, codes)

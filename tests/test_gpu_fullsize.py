@@ -117,14 +117,16 @@ def test_end_to_end_stage_with_codec():
 
 
 @pytest.mark.timeout(600)
-def test_end_to_end_fused_codec_equals_separate_calls():
+@pytest.mark.parametrize("scale_bits", [32, 16])
+def test_end_to_end_fused_codec_equals_separate_calls(scale_bits):
     """What bench.py times at this size: swarm_stage_forward_coded / swarm_stage_backward_coded on 8192 x 4096 (the
     256 x 256 GEMM tile with the int8-encoding epilogue and its non-temporal copy, LayerNorm forward decoding and
     LayerNorm backward encoding at 16 rows per workgroup).  Codes, scales, the decoded input and every parameter
     gradient must equal, bit for bit, those of swarm_codec_decode -> swarm_stage_forward / backward ->
-    swarm_codec_encode, which the test above ties to the oracle."""
+    swarm_codec_encode, which the test above ties to the oracle - with fp32 block scales and with 16-bit ones (the
+    *_s16 twins of the codec and of the fused calls)."""
     from test_gpu_coded import _run
-    _run(synth.WORKLOADS["e2e_bf16_d4096"])
+    _run(synth.WORKLOADS["e2e_bf16_d4096"], scale_bits)
 
 
 def test_gemm_encoding_epilogue_large_tiles():
