@@ -211,6 +211,25 @@ def cpu_baseline(wl):
 
     seq = min(wl.seq, 2048)
     cores = blas_threads()
+    if 96.0 * wl.tokens * wl.d_model * wl.d_model * apps < 2e12:
+        # small workloads (the fp32 block, the d_model 1024 stage and block): the WHOLE workload, median of three runs
+        def full(dt):
+            params, x, G = synth.make_params(wl), synth.make_x_in(wl), synth.make_grad_out(wl)
+            ts = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                osg.stage_forward(params, x, wl.n_heads, wl.n_repeat, wl.ln_eps, dt, kind=wl.block)
+                osg.stage_backward(params, x, G, osg.zero_grads(params, dt), wl.n_heads, wl.n_repeat, wl.ln_eps, dt,
+                                   kind=wl.block)
+                ts.append(time.perf_counter() - t0)
+            return sorted(ts)[1]
+        t32, t64 = full(np.float32), full(np.float64)
+        with threadpool_limits(limits=1):
+            t1 = full(np.float32)
+        return {"value": wl.tokens / t32, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                "sample": "fp32 numpy oracle, the whole workload (%d tokens, %d block applications, fwd + recomputing "
+                          "bwd), median of 3 runs: %.2f s on %d BLAS threads" % (wl.tokens, apps, t32, cores),
+                "fp64_all_cores_tokens_per_s": wl.tokens / t64, "fp32_one_thread_tokens_per_s": wl.tokens / t1}
     t32 = run(seq, np.float32)
     t64 = run(seq, np.float64)
     small = min(seq, 512)

@@ -5,6 +5,13 @@
                                                           [kernel name prefix = gemm_bf16 [largest]]
 
     python profile_summary.py counters <counter_collection.csv> [more .csv ...]
+    python profile_summary.py durations <dir>/<prefix>_kernel_trace.csv <kernel name prefix> [<bytes per launch>]
+    python profile_summary.py streaming <dir>/<prefix>_kernel_trace.csv <tokens> <d_model> <d_ffn>
+
+`durations` prints a JSON object with the number of launches, the average, median and minimum kernel duration
+(End_Timestamp - Start_Timestamp of the kernel trace) of the kernels whose name starts with the prefix, and GB/s
+for the given algorithmic bytes per launch.  `streaming` prints a table of the HBM-bound kernels of a stage step
+(LayerNorm, column sums, codec, attention row sums) with their algorithmic bytes per launch and GB/s against 8 TB/s.
 
 `counters` prints, per kernel family (GEMM: per instantiation; others: name up to the template arguments), the sum over all launches of every
 counter found in the given rocprofv3 --pmc runs of bench.py, and each counter as a fraction of SQ_BUSY_CU_CYCLES
@@ -107,5 +114,51 @@ def counters(*paths: str) -> None:
         print()
 
 
+def _durations(path: str):
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        acc[_short(r["Kernel_Name"])].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    return acc
+
+
+def durations(path: str, prefix: str, nbytes: str = "0") -> None:
+    acc = _durations(path)
+    v = sorted(x for k, vals in acc.items() if k.startswith(prefix) for x in vals)
+    out = {"kernel_prefix": prefix, "launches": len(v), "avg_us": round(sum(v) / len(v), 2),
+           "median_us": round(v[len(v) // 2], 2), "min_us": round(v[0], 2)}
+    if float(nbytes) > 0:
+        out["bytes_per_launch"] = float(nbytes)
+        out["GBps_at_median"] = round(float(nbytes) / out["median_us"] / 1e3, 1)
+        out["frac_of_8TBps_at_median"] = round(float(nbytes) / out["median_us"] / 1e3 / 8000.0, 3)
+    print(json.dumps(out))
+
+
+def streaming(path: str, tokens: str, d_model: str, d_ffn: str) -> None:
+    T, d, f = int(tokens), int(d_model), int(d_ffn)
+    acc = _durations(path)
+    # algorithmic bytes per launch (bf16 tensors): what the kernel has to read and write once
+    table = [("ln_fwd_kernel<unsigned short, 8, false", "LayerNorm forward", 4.0 * T * d, "x in, y out"),
+             ("ln_fwd_kernel<unsigned short, 8, true", "LayerNorm forward, int8 input decoded", (1.0625 + 4.0) * T * d,
+              "codes + scales in, x and y out"),
+             ("ln_bwd_kernel<unsigned short, 2, false", "LayerNorm backward", 8.0 * T * d, "dy, x, residual gradient in, dx out"),
+             ("ln_bwd_kernel<unsigned short, 2, true", "LayerNorm backward, int8 output encoded", (6.0 + 1.0625) * T * d,
+              "dy, x, residual gradient in, codes + scales out"),
+             ("colsum_partial_kernel", "bias-gradient column sums (four widths, average)", 2.0 * T * (5 * d + f) / 4,
+              "gradient tensor in"),
+             ("swarm::codec_encode_kernel", "codec encode", 3.0625 * T * d, "x in, codes + scales out"),
+             ("swarm::codec_decode_kernel", "codec decode", 3.0625 * T * d, "codes + scales in, x out"),
+             ("attn_delta_kernel", "attention backward row sums", 4.0 * T * d, "o, do in")]
+    print("| kernel | what | launches | median us | algorithmic bytes per launch | GB/s | of 8 TB/s |")
+    print("|---|---|---|---|---|---|---|")
+    for prefix, what, nbytes, note in table:
+        v = sorted(x for k, vals in acc.items() if k.startswith(prefix) for x in vals)
+        if not v:
+            continue
+        med = v[len(v) // 2]
+        print("| `%s` | %s (%s) | %d | %.1f | %.4g | %.0f | %.2f |" % (prefix.split("<")[0], what, note, len(v), med, nbytes,
+                                                                 nbytes / med / 1e3, nbytes / med / 1e3 / 8000.0))
+
+
 if __name__ == "__main__":
-    {"stats": stats, "pmc": pmc, "counters": counters}[sys.argv[1]](*sys.argv[2:])
+    {"stats": stats, "pmc": pmc, "counters": counters, "durations": durations,
+     "streaming": streaming}[sys.argv[1]](*sys.argv[2:])
