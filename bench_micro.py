@@ -162,7 +162,7 @@ def run_stamps(lib, out):
             idx = idx[np.argsort(s[idx, 0])]
             gaps += [s[b, 0] - s[a, 3] for a, b in zip(idx[:-1], idx[1:])]
             last_end.append(s[idx[-1], 3])
-        by_x = [loop[xcc == x].mean() for x in sorted(set(xcc.tolist()))]
+        by_x = [float(loop[xcc == x].mean()) for x in sorted(set(xcc.tolist()))]
         ghz = t[:, 8].astype(np.float64) / (loop * 1e3)                 # shader cycles in the loop / its wall time
         ghz_x = [float(ghz[xcc == x].mean()) for x in sorted(set(xcc.tolist()))]
         flops_tile = 2.0 * 256 * 256 * K
