@@ -1,9 +1,9 @@
 /*
  * swarm_head.h - C ABI of the first- and last-stage extras of the language model (MI355X, gfx950).
  *
- * Section 4.3: "the first stage also contains the embedding layer, and the last stage includes the language
- * modeling head" (the appendix "Detailed Performance Comparison" describes a last stage that holds only the
- * vocabulary projection).  The paper prints no formulas for them; the plain definitions are used:
+ * The first-stage embedding layer and the last-stage language-modelling head of the Section 4.3 model (the
+ * appendix "Detailed Performance Comparison" describes a last stage that holds only the vocabulary projection).
+ * The paper prints no formulas for them; the plain definitions are used:
  *     embedding:    x[t, :] = table[token[t], :]
  *     head + loss:  n = LayerNorm(x; ln_g, ln_b);  logits[t, v] = n[t, :] . w_vocab[v, :]  (no bias);
  *                   loss = mean over the T tokens of ( logsumexp_{v < vocab} logits[t, v] - logits[t, target[t]] ).
