@@ -212,3 +212,15 @@ def test_headers_are_c99_and_binding_structs_match_their_layout(tmp_path):
         cxx = tmp_path / "probe.cpp"
         cxx.write_text("\n".join('#include "%s"' % h for h in sorted(os.listdir(inc)) if h.endswith(".h")) + "\nint main() { return 0; }\n")
         subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cxx)], check=True)
+
+
+def test_lamb_static_validation_without_gpu(lib):
+    """The entry point without workspace rejects what the host can see before it looks up its device scratch."""
+    cfg = binding._LambConfig(1e-3, 0.9, 0.95, 1e-6, 0.01, 1.0, 1)
+    f = lib.swarm_lamb_step_static
+    assert f(C.byref(cfg), 1024, None, None, 0, 4096, 8192, 12288, None, None) == -1             # null master weights
+    assert f(C.byref(cfg), 0, 4096, None, 0, 8192, 12288, 16384, None, None) == -2                # empty tensor
+    assert f(C.byref(cfg), 1024, 4100, None, 0, 8192, 12288, 16384, None, None) == -2             # misaligned
+    assert f(C.byref(cfg), sw.SWARM_LAMB_STATIC_MAX_ELEMS + 1, 4096, None, 0, 8192, 12288, 16384, None, None) == -4
+    bad = binding._LambConfig(1e-3, 1.5, 0.95, 1e-6, 0.01, 1.0, 1)
+    assert f(C.byref(bad), 1024, 4096, None, 0, 8192, 12288, 16384, None, None) == -2
