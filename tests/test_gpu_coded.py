@@ -82,12 +82,14 @@ def test_coded_equals_unfused(shape, scale_bits):
 
 
 @pytest.mark.parametrize("scale_bits", [32, 16])
-def test_coded_against_oracle_chain(scale_bits):
+@pytest.mark.parametrize("shape", [(256, 2, 512, 96, 2, 1, 2), (512, 4, 1024, 75, 3, 2, 1), (1024, 8, 4096, 320, 1, 1, 1)])
+def test_coded_against_oracle_chain(scale_bits, shape):
     """decode (oracle) -> oracle stage -> compare decoded GPU outputs within the bf16 tolerance plus half a
     quantisation step of the output codec; the GPU's codes and scales are also the oracle codec's on the GPU's
     own decoded values (re-encoding what was decoded gives the same codes)."""
-    wl = synth.Workload(name="coded", dtype="bf16", d_model=256, n_heads=2, d_ffn=512, seq=96, batch=2,
-                        n_layers=1, n_repeat=2, grad_sigma=1e-2, seed=3)
+    d, H, f, S, B, L, R = shape      # heads of 128 and of 64, shared and distinct blocks, a ragged token count
+    wl = synth.Workload(name="coded", dtype="bf16", d_model=d, n_heads=H, d_ffn=f, seq=S, batch=B,
+                        n_layers=L, n_repeat=R, grad_sigma=1e-2, seed=3 + d)
     params, cx, sx, cg, sg, cy, sy, cgi, sgi = _run(wl, scale_bits)
     shape = (wl.batch, wl.seq, wl.d_model)
     x = ocodec.bf16_bits_to_f32(ocodec.decode(cx, sx, out="bf16")).reshape(shape)
