@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Micro-benchmarks behind the roofline discussion of the bf16 MFMA GEMM (one MI355X).
 
-    python bench_micro.py [--what mfma,lds,stamps] [--json PATH]
+    python bench_micro.py [--what mfma,lds,stamps,data] [--json PATH]
 
   mfma   : a loop of nothing but MFMAs on register operands, in the GEMM kernel's shape (8 wavefronts per workgroup,
            two per SIMD, 128 accumulator registers per lane), for both bf16 MFMA shapes and for constant and random
@@ -11,6 +11,9 @@
   stamps : the 256 x 256 GEMM kernel of the instrumented build with wall-clock stamps at four points of every workgroup
            (first loads | loop | epilogue | gap to the next workgroup on the same compute unit), on the three layouts
            at the config-5 shapes
+  data   : the GEMM and the attention kernels as the stage calls them (config-5 shapes), timed on random operands, on
+           all-zero and on all-one operands: same instruction stream, same memory traffic, different switching
+           activity in the matrix pipes and on the data paths, hence a different clock
 
 Everything runs through libswarm_hooks.so (the instrumented build); prints a Markdown summary, optionally a JSON file.
 """
@@ -188,9 +191,69 @@ def run_stamps(lib, out):
     print()
 
 
+def run_data(lib, out):
+    lib.swarm_kernel_gemm.restype = C.c_int
+    lib.swarm_kernel_gemm.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_void_p]
+    lib.swarm_kernel_attention_fwd.restype = C.c_int
+    lib.swarm_kernel_attention_fwd.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p] + [C.c_int] * 4 + [C.c_void_p]
+    lib.swarm_kernel_attention_bwd.restype = C.c_int
+    lib.swarm_kernel_attention_bwd.argtypes = [C.c_int] + [C.c_void_p] * 6 + [C.c_int] * 4 + [C.c_void_p]
+    bf = torch.bfloat16
+    fills = (("random", lambda *sh: torch.randn(*sh, device="cuda").to(bf)),
+             ("zeros", lambda *sh: torch.zeros(*sh, device="cuda", dtype=bf)),
+             ("ones", lambda *sh: torch.ones(*sh, device="cuda", dtype=bf)),
+             ("random again", lambda *sh: torch.randn(*sh, device="cuda").to(bf)))
+
+    def timed(f, iters):
+        for _ in range(5):
+            assert f() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+
+    rows = []
+    M, N, K = 8192, 16384, 4096
+    Bt, S, H, dh = 4, 2048, 32, 128
+    d = H * dh
+    for name, fill in fills:
+        A, W, Cm = fill(M, K), fill(N, K), torch.empty(M, N, device="cuda", dtype=bf)
+        gemm = lambda: lib.swarm_kernel_gemm(1, M, N, K, A.data_ptr(), K, 0, W.data_ptr(), K, 0, Cm.data_ptr(), N, 0,
+                                             None, None, 0, None, 0, None)
+        us_g = timed(gemm, 20)
+        del A, W, Cm
+        qkv, do = fill(Bt, S, 3 * d), fill(Bt, S, d)
+        o = torch.empty(Bt, S, d, dtype=bf, device="cuda")
+        lse, delta = torch.empty(Bt, H, S, device="cuda"), torch.empty(Bt, H, S, device="cuda")
+        dqkv = torch.empty_like(qkv)
+        fwd = lambda: lib.swarm_kernel_attention_fwd(1, qkv.data_ptr(), o.data_ptr(), lse.data_ptr(), Bt, S, H, dh, None)
+        bwd = lambda: lib.swarm_kernel_attention_bwd(1, qkv.data_ptr(), o.data_ptr(), do.data_ptr(), lse.data_ptr(),
+                                                     delta.data_ptr(), dqkv.data_ptr(), Bt, S, H, dh, None)
+        us_f = timed(fwd, 30)
+        us_b = timed(bwd, 15)
+        rows.append({"operands": name, "gemm_us": round(us_g, 1), "gemm_TFLOPs": round(2.0 * M * N * K / us_g * 1e-6, 1),
+                     "attention_fwd_us": round(us_f, 1), "attention_bwd_us": round(us_b, 1)})
+    out["data"] = rows
+    print("## Kernel time against operand data (same kernels, same shapes, same traffic)\n")
+    print("GEMM %d x %d x %d (forward layout, plain store); causal attention B = %d, S = %d, H = %d, d_head = %d.\n"
+          % (M, N, K, Bt, S, H, dh))
+    print("| operands | GEMM us | GEMM TFLOP/s | attention forward us | attention backward us |")
+    print("|---|---|---|---|---|")
+    for r in rows:
+        print("| %s | %.1f | %.1f | %.1f | %.1f |" % (r["operands"], r["gemm_us"], r["gemm_TFLOPs"],
+                                                   r["attention_fwd_us"], r["attention_bwd_us"]))
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="mfma,lds,stamps")
+    ap.add_argument("--what", default="mfma,lds,stamps,data")
     ap.add_argument("--json", default=None)
     args = ap.parse_args()
     import paper_2301_11913_amd as sw
@@ -199,7 +262,7 @@ def main():
     out = {}
     print("# Micro-benchmarks behind the GEMM roofline (MI355X; nominal %.1f GHz, 256 compute units)\n" % NOMINAL_GHZ)
     for w in args.what.split(","):
-        {"mfma": run_mfma, "lds": run_lds, "stamps": run_stamps}[w](lib, out)
+        {"mfma": run_mfma, "lds": run_lds, "stamps": run_stamps, "data": run_data}[w](lib, out)
     if args.json:
         with open(args.json, "w") as f:
             json.dump(out, f, indent=1)
