@@ -116,6 +116,44 @@ def gemm_roofline(step, steps, ms_per_step, workload):
     if att:
         out["attainable_peak"] = att
         out["frac_of_attainable"] = round(achieved / att, 4)
+    if table:
+        out["operand_data"] = gemm_on_constant_operands(table[0]["M"], table[0]["N"], table[0]["K"])
+    return out
+
+
+def gemm_on_constant_operands(M, N, K):
+    """The step's most expensive product (forward layout, plain store) on random and on all-zero operands: the same
+    instructions over the same addresses; what differs is the switching activity, hence the clock the chip holds
+    under its power limit.  Context for `frac`, not part of it."""
+    import torch
+    import paper_2301_11913_amd as sw
+    lib = sw.load_hooks_library()
+    lib.swarm_kernel_gemm.restype = C.c_int
+    lib.swarm_kernel_gemm.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_void_p]
+    bf = torch.bfloat16
+    out = {"M": M, "N": N, "K": K, "layout": "forward", "epilogue": "store"}
+    Cm = torch.empty(M, N, device="cuda", dtype=bf)
+    for name, fill in (("random", lambda *sh: torch.randn(*sh, device="cuda").to(bf)),
+                       ("zeros", lambda *sh: torch.zeros(*sh, device="cuda", dtype=bf))):
+        A, W = fill(M, K), fill(N, K)
+        f = lambda: lib.swarm_kernel_gemm(1, M, N, K, A.data_ptr(), K, 0, W.data_ptr(), K, 0, Cm.data_ptr(), N, 0, None,
+                                          None, 0, None, 0, None)
+        for _ in range(3):
+            if f() != 0:
+                return None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        tf = 2.0 * M * N * K * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        out[name + "_TFLOP/s"] = round(tf, 1)
+        out[name + "_frac"] = round(tf / MFMA_BF16_PEAK_TFLOPS, 3)
+        del A, W
     return out
 
 
