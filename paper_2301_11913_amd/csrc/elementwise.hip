@@ -268,7 +268,10 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
   const int row0 = blockIdx.x * rpb;
   for (int b0 = 0; b0 < rpb; b0 += kLnBatch) {
     const int par = (b0 / kLnBatch) & 1;
-    Raw xraw[kLnBatch][NITQ], dyraw[kLnBatch][NITQ];
+    // The residual gradient is only needed behind the barrier.  Where the registers allow it (four more per chunk
+    // and row) it is requested with x and dy and arrives meanwhile; else it is loaded where it is used.
+    constexpr bool kEarlyRes = NITQ * sizeof(T) <= 4;
+    Raw xraw[kLnBatch][NITQ], dyraw[kLnBatch][NITQ], rraw[kLnBatch][kEarlyRes ? NITQ : 1];
     float mu[kLnBatch], rs[kLnBatch];
 #pragma unroll
     for (int r = 0; r < kLnBatch; ++r) {
@@ -282,6 +285,9 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
           const int c = lane + it * 64;
           if (c < cq) {
             xraw[r][it] = V8<T>::load_raw(x + (size_t)row * d + (size_t)(cbase + c) * 8);
+            if constexpr (kEarlyRes) {
+              if (dres) rraw[r][it] = V8<T>::load_raw(dres + (size_t)row * d + (size_t)(cbase + c) * 8);
+            }
             float xv[8], dv[8], g[8];
             V8<T>::unpack(xraw[r][it], xv);
             V8<T>::unpack(graw[it], g);
@@ -334,7 +340,11 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
         const int c = lane + it * 64;
         if (c < cq) {
           float res[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, o[8], xv[8], dv[8], g[8];
-          if (dres) V8<T>::load(dres + (size_t)row * d + (size_t)(cbase + c) * 8, res);
+          if constexpr (kEarlyRes) {
+            if (dres) V8<T>::unpack(rraw[r][it], res);
+          } else {
+            if (dres) V8<T>::load(dres + (size_t)row * d + (size_t)(cbase + c) * 8, res);
+          }
           V8<T>::unpack(xraw[r][it], xv);
           V8<T>::unpack(dyraw[r][it], dv);
           V8<T>::unpack(graw[it], g);
