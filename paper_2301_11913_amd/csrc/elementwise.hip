@@ -142,24 +142,31 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
     const T* xr = x + (size_t)row * d;
     Raw raw[NIT];
     float s = 0.f;
+    // The loads carry no lane predicate (a chunk index past the row's end is clamped to the last chunk, whose value is
+    // then simply not used): a predicated load sits in a branch of its own and is waited for before the next one is
+    // issued, eight memory round trips in a row instead of one.
+    if constexpr (DEC) {
+      uint2 cw[NIT];
+      float sc[NIT];
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int c = lane + it * 64;
-      if (c < nchunk) {
-        if constexpr (DEC) {
-          const size_t e0 = (size_t)row * d + (size_t)c * 8;
-          const uint2 cw = *reinterpret_cast<const uint2*>(codes + e0);
-          const float sc = block_scale_load(scales, e0 >> 6, scales16);
-          const uint32_t w[2] = {cw.x, cw.y};
-          float t[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) t[i] = (float)(int)(int8_t)((w[i >> 2] >> (8 * (i & 3))) & 0xFF) * sc;
-          V8<T>::store(xdec + e0, t);
-          raw[it] = V8<T>::make_raw(t);                                  // the values just stored
-        } else {
-          raw[it] = V8<T>::load_raw(xr + c * 8);
-        }
+      for (int it = 0; it < NIT; ++it) {
+        const size_t e0 = (size_t)row * d + (size_t)min(lane + it * 64, nchunk - 1) * 8;
+        cw[it] = *reinterpret_cast<const uint2*>(codes + e0);
+        sc[it] = block_scale_load(scales, e0 >> 6, scales16);
       }
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int c = lane + it * 64;
+        const uint32_t w[2] = {cw[it].x, cw[it].y};
+        float t[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = (float)(int)(int8_t)((w[i >> 2] >> (8 * (i & 3))) & 0xFF) * sc[it];
+        if (c < nchunk) V8<T>::store(xdec + (size_t)row * d + (size_t)c * 8, t);
+        raw[it] = V8<T>::make_raw(t);                                  // the values just stored
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) raw[it] = V8<T>::load_raw(xr + min(lane + it * 64, nchunk - 1) * 8);
     }
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
@@ -189,17 +196,28 @@ __global__ __launch_bounds__(kLnThreads) void ln_fwd_kernel(const T* __restrict_
     for (int it = 0; it < NIT; ++it) V8<T>::opaque(raw[it]);
     if constexpr (MAXK == 0) {
       T* yr = y + (size_t)row * d;
+      // gamma and beta of all chunks are requested at once, without lane predicates (see the row loads), in two
+      // halves so that they do not double the registers of the kernel
+      constexpr int HN = NIT > 1 ? NIT / 2 : 1;
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int c = lane + it * 64;
-        if (c < nchunk) {
+      for (int h0 = 0; h0 < NIT; h0 += HN) {
+        Raw graw[HN], braw[HN];
+#pragma unroll
+        for (int k = 0; k < HN; ++k) {
+          const int cl = min(lane + (h0 + k) * 64, nchunk - 1);
+          graw[k] = V8<T>::load_raw(gamma + cl * 8);
+          braw[k] = V8<T>::load_raw(beta + cl * 8);
+        }
+#pragma unroll
+        for (int k = 0; k < HN; ++k) {
+          const int c = lane + (h0 + k) * 64;
           float v[8], g[8], b[8], o[8];
-          V8<T>::unpack(raw[it], v);
-          V8<T>::load(gamma + c * 8, g);
-          V8<T>::load(beta + c * 8, b);
+          V8<T>::unpack(raw[h0 + k], v);
+          V8<T>::unpack(graw[k], g);
+          V8<T>::unpack(braw[k], b);
 #pragma unroll
           for (int i = 0; i < 8; ++i) o[i] = (v[i] - mu) * r * g[i] + b[i];
-          V8<T>::store(yr + c * 8, o);
+          if (c < nchunk) V8<T>::store(yr + c * 8, o);
         }
       }
     } else if constexpr (MAXK > 0) {
@@ -273,6 +291,24 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
     constexpr bool kEarlyRes = NITQ * sizeof(T) <= 4;
     Raw xraw[kLnBatch][NITQ], dyraw[kLnBatch][NITQ], rraw[kLnBatch][kEarlyRes ? NITQ : 1];
     float mu[kLnBatch], rs[kLnBatch];
+    if constexpr (MAXK == 0) {
+      // All loads of the batch are issued first and carry no lane predicate (row and chunk indices past the end are
+      // clamped, the values then not used): a predicated load sits in a branch of its own and is waited for before
+      // the next one is issued, eight memory round trips per batch instead of one.
+#pragma unroll
+      for (int r = 0; r < kLnBatch; ++r) {
+        const size_t rowc = (size_t)min(row0 + b0 + r, rows - 1);
+#pragma unroll
+        for (int it = 0; it < NITQ; ++it) {
+          const size_t e0 = rowc * d + (size_t)(cbase + min(lane + it * 64, cq - 1)) * 8;
+          xraw[r][it] = V8<T>::load_raw(x + e0);
+          dyraw[r][it] = V8<T>::load_raw(dy + e0);
+          if constexpr (kEarlyRes) {
+            if (dres) rraw[r][it] = V8<T>::load_raw(dres + e0);
+          }
+        }
+      }
+    }
 #pragma unroll
     for (int r = 0; r < kLnBatch; ++r) {
       const int row = row0 + b0 + r;
@@ -284,9 +320,11 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
         for (int it = 0; it < NITQ; ++it) {
           const int c = lane + it * 64;
           if (c < cq) {
-            xraw[r][it] = V8<T>::load_raw(x + (size_t)row * d + (size_t)(cbase + c) * 8);
-            if constexpr (kEarlyRes) {
-              if (dres) rraw[r][it] = V8<T>::load_raw(dres + (size_t)row * d + (size_t)(cbase + c) * 8);
+            if constexpr (MAXK > 0) {
+              xraw[r][it] = V8<T>::load_raw(x + (size_t)row * d + (size_t)(cbase + c) * 8);
+              if constexpr (kEarlyRes) {
+                if (dres) rraw[r][it] = V8<T>::load_raw(dres + (size_t)row * d + (size_t)(cbase + c) * 8);
+              }
             }
             float xv[8], dv[8], g[8];
             V8<T>::unpack(xraw[r][it], xv);
@@ -309,7 +347,6 @@ __global__ __launch_bounds__(kLnThreads) void ln_bwd_kernel(const T* __restrict_
               }
               dyraw[r][it] = V8<T>::make_raw(dv);     // exact: dz values and zeros are of type T
             } else {
-              dyraw[r][it] = V8<T>::load_raw(dy + (size_t)row * d + (size_t)(cbase + c) * 8);
               V8<T>::unpack(dyraw[r][it], dv);
             }
 #pragma unroll
