@@ -72,6 +72,10 @@ def _run(wl, scale_bits=32):
     ("bf16", 1024, 8, 4096, 512, 2, 1, 1),
     ("bf16", 128, 2, 192, 37, 3, 1, 1),
     ("f32", 256, 4, 1024, 64, 2, 1, 1),
+    # widths whose chunks do not fill the last pass of the decoding / encoding LayerNorm kernels' lanes
+    ("bf16", 768, 6, 1536, 40, 2, 1, 1),
+    ("bf16", 1536, 12, 1024, 50, 2, 1, 1),
+    ("bf16", 6144, 48, 1024, 24, 2, 1, 1),
 ])
 @pytest.mark.parametrize("scale_bits", [32, 16])
 def test_coded_equals_unfused(shape, scale_bits):

@@ -45,6 +45,19 @@ def test_small_ragged(dtype, shape):
     _check(wl)
 
 
+@pytest.mark.parametrize("case", [
+    # dtype, d_model, heads: widths whose 8-element chunks do not fill the last pass of the LayerNorm kernels' lanes
+    # (768, 1536, 6144) and the widest model the stage accepts (8192), few tokens
+    ("bf16", 768, 6), ("f32", 768, 12), ("bf16", 1536, 12), ("f32", 1536, 24), ("bf16", 6144, 48), ("f32", 6144, 48),
+    ("bf16", 8192, 64),
+])
+def test_wide_models(case):
+    dtype, d, H = case
+    wl = synth.Workload(name="wide", dtype=dtype, d_model=d, n_heads=H, d_ffn=1024 if d > 2048 else 2 * d, seq=40, batch=2,
+                        n_layers=1, n_repeat=1, grad_sigma=1.0 if dtype == "f32" else 1e-2, seed=99 + d)
+    _check(wl)
+
+
 def test_config2_stage_bf16():
     _check(synth.WORKLOADS["stage2_bf16_d1024"])
 
