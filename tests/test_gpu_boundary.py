@@ -166,6 +166,10 @@ def check(wl, dt=np.float64):
     ("maxout", 512, 64, 33),           # k = 8
     ("maxout", 384, 128, 21),          # k = 3: the one-window-per-thread kernel
     ("maxout", 1024, 512, 512),
+    ("maxout", 768, 384, 45),          # widths that leave the last pass of the LayerNorm kernels' lanes partly empty
+    ("maxout", 1536, 384, 29),
+    ("maxout", 6144, 3072, 19),
+    ("bottleneck", 6144, 512, 23),
 ])
 def test_boundary_layers(dtype, kind, m, c, T):
     check(synth.BoundaryWorkload("b", dtype, kind, m, c, T, 1.0 if dtype == "f32" else 1e-2, seed=700 + m + c + T))
