@@ -544,11 +544,9 @@ swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, v
 swarm_status layernorm_fwd_decode(const int8_t* codes, const void* scales, void* xdec, const void* gamma,
                                   const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
                                   bool bf16, hipStream_t st, bool scales16) {
-  if (bf16)
-    return ln_fwd_dispatch<bf16_raw, true>(nullptr, (const bf16_raw*)gamma, (const bf16_raw*)beta, (bf16_raw*)y,
-                                           mean, rstd, T, d, eps, codes, scales, (bf16_raw*)xdec, st, scales16);
-  return ln_fwd_dispatch<float, true>(nullptr, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, T, d,
-                                      eps, codes, scales, (float*)xdec, st, scales16);
+  if (!bf16) return SWARM_ERR_SHAPE;     // the stage fuses the codec for bf16 activations only
+  return ln_fwd_dispatch<bf16_raw, true>(nullptr, (const bf16_raw*)gamma, (const bf16_raw*)beta, (bf16_raw*)y, mean,
+                                         rstd, T, d, eps, codes, scales, (bf16_raw*)xdec, st, scales16);
 }
 
 size_t layernorm_bwd_scratch_floats(int T, int d) {
@@ -561,7 +559,7 @@ swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, con
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
                            bool bf16, hipStream_t st, int8_t* codes, void* scales, bool scales16) {
   swarm_status s;
-  if (codes && (d % 256)) return SWARM_ERR_SHAPE;
+  if (codes && (d % 256 || !bf16)) return SWARM_ERR_SHAPE;     // the stage fuses the codec for bf16 activations only
   if (bf16) {
     const bf16_raw *a = (const bf16_raw*)dy, *b = (const bf16_raw*)x, *g = (const bf16_raw*)gamma,
                    *r = (const bf16_raw*)dres;
@@ -571,9 +569,7 @@ swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, con
                                                  st);
   } else {
     const float *a = (const float*)dy, *b = (const float*)x, *g = (const float*)gamma, *r = (const float*)dres;
-    s = codes ? ln_bwd_dispatch<float, true>(a, b, mean, rstd, g, r, nullptr, partial, T, d, codes, scales, st, nullptr,
-                                             scales16)
-              : ln_bwd_dispatch<float, false>(a, b, mean, rstd, g, r, (float*)dx, partial, T, d, nullptr, nullptr, st);
+    s = ln_bwd_dispatch<float, false>(a, b, mean, rstd, g, r, (float*)dx, partial, T, d, nullptr, nullptr, st);
   }
   if (s != SWARM_OK) return s;
   const int P = (T + ln_rows_per_block(T) - 1) / ln_rows_per_block(T);

@@ -64,7 +64,8 @@ swarm_status layernorm_fwd(const void* x, const void* gamma, const void* beta, v
 // dx = dres + LN-backward(dy) (dres == nullptr: no residual), dgamma += sum_t dy*xhat, dbeta += sum_t dy.
 // `partial` is scratch of layernorm_bwd_scratch_floats(T, d) floats.
 size_t layernorm_bwd_scratch_floats(int T, int d);
-// With codes != nullptr dx is not stored: its int8 blockwise encoding is (fused stage-exit encode, d % 256 == 0).
+// With codes != nullptr dx is not stored: its int8 blockwise encoding is (fused stage-exit encode, bf16 and
+// d % 256 == 0 only).
 swarm_status layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
                            const void* dres, void* dx, float* dgamma, float* dbeta, float* partial, int T, int d,
                            bool bf16, hipStream_t st, int8_t* codes = nullptr, void* scales = nullptr,
@@ -79,7 +80,7 @@ swarm_status layernorm_fwd_maxout(const void* x, const void* gamma, const void* 
 swarm_status layernorm_bwd_maxout(const void* dz, const void* x, const float* mean, const float* rstd,
                                   const void* gamma, const void* beta, void* dx, float* dgamma, float* dbeta,
                                   float* partial, int T, int d, int k, bool bf16, hipStream_t st);
-// LayerNorm of a row that arrives int8-encoded: xdec receives the decoded row (fused stage-entry decode).
+// LayerNorm of a row that arrives int8-encoded: xdec receives the decoded row (fused stage-entry decode, bf16 only).
 swarm_status layernorm_fwd_decode(const int8_t* codes, const void* scales, void* xdec, const void* gamma,
                                   const void* beta, void* y, float* mean, float* rstd, int T, int d, float eps,
                                   bool bf16, hipStream_t st, bool scales16 = false);

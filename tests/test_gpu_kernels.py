@@ -79,7 +79,11 @@ LAYOUTS = [(False, False), (False, True), (True, True)]
 
 @pytest.mark.parametrize("a_t,b_t", LAYOUTS)
 @pytest.mark.parametrize("shape", [(256, 256, 64), (128, 128, 128), (512, 768, 256), (300, 192, 320),
-                                   (37, 64, 64), (1000, 1088, 200), (4096, 4096, 512), (2048, 4096 + 64, 256 + 64)])
+                                   (37, 64, 64), (1000, 1088, 200), (4096, 4096, 512), (2048, 4096 + 64, 256 + 64),
+                                   # whole tiles but K no multiple of 64: the register-staged kernels without their
+                                   # bounds checks (128 x 128 and, from 160 big tiles on, 256 x 256), and a ragged M there
+                                   (256, 384, 96), (4096, 2560, 96), (4104, 2560, 96),
+                                   (40, 24, 20)])         # K no multiple of 8: the scalar kernel
 def test_gemm_layouts(a_t, b_t, shape):
     M, N, K = shape
     if a_t and M % 8:
@@ -227,7 +231,8 @@ def _attn_ref(qkv, dout, B, S, H, dh):
 
 @pytest.mark.parametrize("shape", [(2, 128, 2, 64), (1, 512, 3, 128), (3, 37, 2, 128), (2, 200, 1, 64),
                                    (1, 1, 2, 64), (1, 1000, 2, 128), (2, 2048, 2, 128),
-                                   (1, 4100, 1, 128), (1, 2500, 2, 64), (5, 129, 3, 128), (1, 191, 1, 64)])
+                                   (1, 4100, 1, 128), (1, 2500, 2, 64), (5, 129, 3, 128), (1, 191, 1, 64),
+                                   (2, 70, 3, 32)])       # a head size only the direct kernels take
 def test_attention_bf16(shape):
     B, S, H, dh = shape
     lib = _attn_lib()
