@@ -266,16 +266,14 @@ swarm_status gemm_bf16_launch(const GemmArgs& g, hipStream_t st) {
   k.rope = g.rope; k.rope_S = g.rope_S; k.rope_dh = g.rope_dh; k.rope_cols = g.rope_cols; k.split = g.split;
   k.ksplit = 1; k.part = nullptr; k.stream = 0; k.stamps = nullptr;
   const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  // What arrives here has a ragged M, N or K (whole tiles with K % 64 == 0 went to the direct-to-LDS kernels above):
+  // the bounds-checked instantiations only.
   if (big_tiles >= 160) {
     k.tiles_m = (g.M + 255) / 256; k.tiles_n = (g.N + 255) / 256;
-    const bool guard = (g.M % 256) || (g.N % 256) || (g.K % BK);
-    return guard ? launch_layout<256, 256, 2, 4, true>(k, g.a_trans, g.b_trans, st)
-                 : launch_layout<256, 256, 2, 4, false>(k, g.a_trans, g.b_trans, st);
+    return launch_layout<256, 256, 2, 4, true>(k, g.a_trans, g.b_trans, st);
   }
   k.tiles_m = (g.M + 127) / 128; k.tiles_n = (g.N + 127) / 128;
-  const bool guard = (g.M % 128) || (g.N % 128) || (g.K % BK);
-  return guard ? launch_layout<128, 128, 2, 2, true>(k, g.a_trans, g.b_trans, st)
-               : launch_layout<128, 128, 2, 2, false>(k, g.a_trans, g.b_trans, st);
+  return launch_layout<128, 128, 2, 2, true>(k, g.a_trans, g.b_trans, st);
 }
 
 }  // namespace swarm

@@ -172,7 +172,8 @@ def check(wl, dt=np.float64):
     ("bottleneck", 6144, 512, 23),
     # every (row width class of the fused LayerNorm + maxout kernels, window) pair not covered above
     ("maxout", 1024, 256, 40), ("maxout", 1024, 128, 40), ("maxout", 2048, 1024, 24), ("maxout", 2048, 256, 24),
-    ("maxout", 4096, 1024, 16), ("maxout", 4096, 512, 16), ("maxout", 8192, 2048, 12), ("maxout", 8192, 1024, 12),
+    ("maxout", 4096, 2048, 16), ("maxout", 4096, 1024, 16), ("maxout", 4096, 512, 16), ("maxout", 8192, 2048, 12),
+    ("maxout", 8192, 1024, 12),
 ])
 def test_boundary_layers(dtype, kind, m, c, T):
     check(synth.BoundaryWorkload("b", dtype, kind, m, c, T, 1.0 if dtype == "f32" else 1e-2, seed=700 + m + c + T))

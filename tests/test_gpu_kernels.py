@@ -80,8 +80,8 @@ LAYOUTS = [(False, False), (False, True), (True, True)]
 @pytest.mark.parametrize("a_t,b_t", LAYOUTS)
 @pytest.mark.parametrize("shape", [(256, 256, 64), (128, 128, 128), (512, 768, 256), (300, 192, 320),
                                    (37, 64, 64), (1000, 1088, 200), (4096, 4096, 512), (2048, 4096 + 64, 256 + 64),
-                                   # whole tiles but K no multiple of 64: the register-staged kernels without their
-                                   # bounds checks (128 x 128 and, from 160 big tiles on, 256 x 256), and a ragged M there
+                                   # whole tiles but K no multiple of 64: the register-staged kernels (128 x 128
+                                   # and, from 160 big tiles on, 256 x 256), and a ragged M there
                                    (256, 384, 96), (4096, 2560, 96), (4104, 2560, 96),
                                    (40, 24, 20)])         # K no multiple of 8: the scalar kernel
 def test_gemm_layouts(a_t, b_t, shape):
