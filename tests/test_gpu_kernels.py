@@ -234,10 +234,21 @@ def _attn_ref(qkv, dout, B, S, H, dh):
                                    (1, 4100, 1, 128), (1, 2500, 2, 64), (5, 129, 3, 128), (1, 191, 1, 64),
                                    (2, 70, 3, 32)])       # a head size only the direct kernels take
 def test_attention_bf16(shape):
+    _attention_case(shape, 1.5)
+
+
+@pytest.mark.parametrize("shape", [(1, 300, 2, 128), (2, 200, 2, 64), (1, 1100, 1, 128)])
+def test_attention_bf16_peaked_scores(shape):
+    """Scores with a standard deviation of several tens: nearly one-hot softmax rows, the running reference of the
+    exponentials is raised again and again along a row, earlier keys underflow to exact zeros."""
+    _attention_case(shape, 6.0)
+
+
+def _attention_case(shape, std):
     B, S, H, dh = shape
     lib = _attn_lib()
     d = H * dh
-    qkv = _bf(synth.normal(S + dh, "qkv", (B, S, 3 * d), std=1.5))
+    qkv = _bf(synth.normal(S + dh, "qkv", (B, S, 3 * d), std=std))
     dout = _bf(synth.normal(S + dh, "dout", (B, S, d)))
     ro, rlse, rdqkv = _attn_ref(qkv.double().numpy(), dout.double().numpy(), B, S, H, dh)
     qd, dod = qkv.cuda(), dout.cuda()
