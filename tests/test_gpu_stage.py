@@ -58,6 +58,28 @@ def test_wide_models(case):
     _check(wl)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_rows(dtype):
+    """Token rows the LayerNorm has nothing to normalise (all features equal: variance 0, the row statistics rest on
+    eps alone), an all-zero row and an all-zero gradient row, next to ordinary ones.  bf16 takes the zero rows only: a
+    constant row of -3 makes the hidden stream -3 + (attention output of a few hundredths), which bf16 storage
+    quantises to two or three levels before the second LayerNorm divides by their spread; the fp64 oracle keeps
+    those digits, and the difference (7 % on the weight gradients) is the storage format's, not a kernel's."""
+    wl = synth.Workload(name="degenerate", dtype=dtype, d_model=256, n_heads=2, d_ffn=512, seq=24, batch=2, n_layers=2,
+                        n_repeat=1, grad_sigma=1.0 if dtype == "f32" else 1e-2, seed=5)
+    params, x, G = synth.make_params(wl), synth.make_x_in(wl).copy(), synth.make_grad_out(wl).copy()
+    if dtype == "f32":
+        x[0, 3, :] = 0.75
+        x[1, 7, :] = -3.0
+    x[1, 0, :] = 0.0
+    G[0, 5, :] = 0.0
+    gpu = run_gpu(wl, params, x, G)
+    ref = run_oracle(wl, params, x, G)
+    errs, bad = compare(gpu, ref, TOL[wl.dtype])
+    assert not bad, bad
+    assert np.all(np.isfinite(gpu["x_out"])) and np.all(np.isfinite(gpu["grad_in"]))
+
+
 def test_config2_stage_bf16():
     _check(synth.WORKLOADS["stage2_bf16_d1024"])
 
