@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Micro-benchmarks behind the roofline discussion of the bf16 MFMA GEMM (one MI355X).
 
-    python bench_micro.py [--what mfma,lds,stamps,data] [--json PATH]
+    python bench_micro.py [--what mfma,lds,stamps,data,vendor] [--json PATH]
 
   mfma   : a loop of nothing but MFMAs on register operands, in the GEMM kernel's shape (8 wavefronts per workgroup,
            two per SIMD, 128 accumulator registers per lane), for both bf16 MFMA shapes and for constant and random
@@ -14,8 +14,11 @@
   data   : the GEMM and the attention kernels as the stage calls them (config-5 shapes), timed on random operands, on
            all-zero and on all-one operands: same instruction stream, same memory traffic, different switching
            activity in the matrix pipes and on the data paths, hence a different clock
+  vendor : the GEMM kernel (plain store) beside the ROCm BLAS that torch.matmul calls, same operands, same run,
+           alternating, on the products of the config-5 stage, random and all-zero operands; context for the roofline
+           fraction (what the vendor's kernels reach on this machine and this data), never on the stage path
 
-Everything runs through libswarm_hooks.so (the instrumented build); prints a Markdown summary, optionally a JSON file.
+Everything else runs through libswarm_hooks.so (the instrumented build); prints a Markdown summary, optionally a JSON file.
 """
 from __future__ import annotations
 
@@ -131,7 +134,8 @@ def run_stamps(lib, out):
     print("| product (M x N x K, layout, epilogue) | kernel | first loads | loop (p10 - p90) | epilogue | gap to next workgroup | "
           "loop alone TFLOP/s | launch TFLOP/s | loop time by XCD (min - max) | last tile ends after first idle CU |\n"
           "|---|---|---|---|---|---|---|---|---|---|")
-    for (M, N, K, a_t, b_t, epi, label) in ((8192, 16384, 4096, 0, 0, 3, "forward, bias + GeLU"),
+    for (M, N, K, a_t, b_t, epi, label) in ((8192, 12288, 4096, 0, 0, 1, "forward, bias"),
+                                           (8192, 16384, 4096, 0, 0, 3, "forward, bias + GeLU"),
                                            (8192, 16384, 4096, 0, 1, 4, "dgrad, x GeLU'"),
                                            (8192, 4096, 16384, 0, 0, 2, "forward, bias + residual"),
                                            (16384, 4096, 8192, 1, 1, 5, "wgrad, fp32 +=")):
@@ -251,6 +255,75 @@ def run_data(lib, out):
     print()
 
 
+def run_vendor(lib, out):
+    lib.swarm_kernel_gemm.restype = C.c_int
+    lib.swarm_kernel_gemm.argtypes = [C.c_int] * 4 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                      C.c_void_p, C.c_int, C.c_void_p]
+    bf = torch.bfloat16
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(f, iters=12):
+        for _ in range(4):
+            f()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); f(); e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3)
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    # (name, M, N, K, A stored [K, M], B stored [K, N])
+    products = (("forward (FFN1)", 8192, 16384, 4096, 0, 0), ("forward (QKV)", 8192, 12288, 4096, 0, 0),
+                ("forward (FFN2)", 8192, 4096, 16384, 0, 0), ("dgrad (FFN1)", 8192, 4096, 16384, 0, 1),
+                ("dgrad (FFN2)", 8192, 16384, 4096, 0, 1), ("wgrad (FFN1)", 16384, 4096, 8192, 1, 1),
+                ("wgrad (out-proj)", 4096, 4096, 8192, 1, 1))
+    rows = []
+    for name, M, N, K, a_t, b_t in products:
+        for kind in ("random", "zeros"):
+            mk = (lambda *sh: torch.randn(*sh, device="cuda").to(bf)) if kind == "random" else \
+                 (lambda *sh: torch.zeros(*sh, device="cuda", dtype=bf))
+            A = mk(K, M) if a_t else mk(M, K)
+            B = mk(K, N) if b_t else mk(N, K)
+            Co, Cv = torch.empty(M, N, device="cuda", dtype=bf), torch.empty(M, N, device="cuda", dtype=bf)
+            Av = A.t() if a_t else A
+            Bv = B if b_t else B.t()
+
+            def ours():
+                assert lib.swarm_kernel_gemm(1, M, N, K, A.data_ptr(), A.shape[1], a_t, B.data_ptr(), B.shape[1], b_t,
+                                             Co.data_ptr(), N, 0, None, None, 0, None, 0, stream) == 0
+
+            def vendor():
+                torch.matmul(Av, Bv, out=Cv)
+
+            us = [timed(ours), timed(vendor), timed(ours), timed(vendor)]
+            if kind == "random":     # same product on both sides (fp32 accumulation, one bf16 rounding)
+                diff = float((Co.float() - Cv.float()).abs().max() / Cv.float().abs().max())
+            else:
+                diff = 0.0
+            fl = 2.0 * M * N * K * 1e-6
+            rows.append({"product": name, "M": M, "N": N, "K": K, "operands": kind,
+                         "this_us": [round(us[0], 1), round(us[2], 1)], "vendor_us": [round(us[1], 1), round(us[3], 1)],
+                         "this_TFLOPs": round(fl / min(us[0], us[2]), 1), "vendor_TFLOPs": round(fl / min(us[1], us[3]), 1),
+                         "max_normalised_difference": diff})
+            del A, B, Co, Cv
+    out["vendor"] = rows
+    print("## This GEMM kernel beside the ROCm BLAS behind torch.matmul (same operands, same run, alternating)\n")
+    print("bf16 in, fp32 accumulation, bf16 out, plain store; median of 12 launches, two rounds each, the better round "
+          "counted; torch %s.\n" % torch.__version__)
+    print("| product | M x N x K | operands | this kernel us | vendor us | this TFLOP/s (of 2500) | vendor TFLOP/s (of 2500) |")
+    print("|---|---|---|---|---|---|---|")
+    for r in rows:
+        print("| %s | %d x %d x %d | %s | %s | %s | %.1f (%.3f) | %.1f (%.3f) |" % (
+            r["product"], r["M"], r["N"], r["K"], r["operands"], " / ".join("%.1f" % v for v in r["this_us"]),
+            " / ".join("%.1f" % v for v in r["vendor_us"]), r["this_TFLOPs"], r["this_TFLOPs"] / 2500.0,
+            r["vendor_TFLOPs"], r["vendor_TFLOPs"] / 2500.0))
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--what", default="mfma,lds,stamps,data")
@@ -262,7 +335,7 @@ def main():
     out = {}
     print("# Micro-benchmarks behind the GEMM roofline (MI355X; nominal %.1f GHz, 256 compute units)\n" % NOMINAL_GHZ)
     for w in args.what.split(","):
-        {"mfma": run_mfma, "lds": run_lds, "stamps": run_stamps, "data": run_data}[w](lib, out)
+        {"mfma": run_mfma, "lds": run_lds, "stamps": run_stamps, "data": run_data, "vendor": run_vendor}[w](lib, out)
     if args.json:
         with open(args.json, "w") as f:
             json.dump(out, f, indent=1)

@@ -511,6 +511,335 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
 #endif
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// The 256 x 256 tile on FOUR wavefronts of 128 x 128, both operands k-contiguous (forward products).  A wavefront's
+// sub-step reads 8 + 8 fragments for 64 MFMAs where the 128 x 64 sub-tiles above read 8 + 4 for 32: a third fewer
+// LDS bytes per flop, and LDS reads are what costs clock next to the matrix pipes.  One wavefront per SIMD has no
+// partner to cover its waits, so nothing here may wait for anything recent:
+//   - the 256 accumulator registers live in the accumulation half of the register file and the MFMAs work on them
+//     in place (inline assembly: left to the compiler the products are formed in vector registers and copied over);
+//   - both fragment sets are double-buffered (128 vector registers) and every read of the next sub-step is requested
+//     during the first half of the current one, with plain instructions: the compiler turns each wait for an LDS read
+//     it knows of into a wait for all of them while global -> LDS loads are in flight, and would put one in front of
+//     every sub-step;
+//   - the per-slice barrier sits behind the second MFMA of the slice's second sub-step, the reads of the next slice
+//     and the refill of the freed stage follow it.
+typedef uint32_t u32x4_frag __attribute__((ext_vector_type(4)));
+template <int BYTE_OFF>
+__device__ __forceinline__ bf16x8 lds_frag_plain(uint32_t addr) {
+  static_assert(BYTE_OFF >= 0 && BYTE_OFF < 65536, "ds offset field");
+  u32x4_frag v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(BYTE_OFF) : "memory");
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Epilogue of the four-wavefront kernel.  Its MFMAs take the B fragment as the first operand, so a lane's block
+// registers are FOUR CONSECUTIVE COLUMNS of one row: blk[i][j][r] = C(row0 + 16 i + lane % 16, col0 + 16 j +
+// 4 (lane / 16) + r).  One wavefront alone on its SIMD issues vector instructions at about half the rate two reach
+// together, so the epilogue is kept short: the arithmetic (bias, residual) runs on the accumulator layout, the
+// results are rounded to bf16 and turned into row order through ONE pass over a private 128 x 128 bf16 patch
+// (8-byte cells in, 16-byte row pieces out), and the residual rows take the same patch the other way (16-byte row
+// pieces in, the lane's own 8-byte cell out).  Same arithmetic, in the same order, as gemm_epilogue: the two kernels
+// give the same bits.  Handles EPI_STORE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_RESID_ENCODE and EPI_PART_F32.
+constexpr int kW4PatchPitch = 272;                       // bytes per patch row: 256 + 16 (rows 4 banks apart)
+constexpr int kW4PatchBytes = 128 * kW4PatchPitch;       // per wavefront
+
+inline bool w4_epilogue_ok(int epi) {
+  return epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_RESID_ENCODE;
+}
+
+// one accumulator register into a vector register, where it is used (left to itself the compiler moves all 256
+// over at the start of the epilogue and spills)
+__device__ __forceinline__ float acc_read(const float& a) {
+  float v;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
+template <int EPI, bool NT>
+__device__ __forceinline__ void w4_epilogue_nt(const KArgs& p, const Acc16<4, 4>& acc, int row0, int col0, int lane,
+                                               char* patch) {
+  const int l16 = lane & 15, q = lane >> 4;
+  if constexpr (EPI == EPI_PART_F32) {   // fp32 partial tile of a product cut along K: 16 bytes per lane, as they are
+    float* c = reinterpret_cast<float*>(p.C) + (size_t)(row0 + l16) * p.ldc + col0 + 4 * q;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float4 v = make_float4(acc_read(acc.blk[i][j][0]), acc_read(acc.blk[i][j][1]),
+                                     acc_read(acc.blk[i][j][2]), acc_read(acc.blk[i][j][3]));
+        *reinterpret_cast<float4*>(c + (size_t)(16 * i) * p.ldc + 16 * j) = v;
+        if (j == 7) __builtin_amdgcn_sched_barrier(0);
+      }
+    return;
+  }
+  constexpr bool has_aux = EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_RESID_ENCODE;
+  // row-order accesses: 16 lanes cover the 256 bytes of a patch row, an instruction covers 4 rows
+  const int c16 = lane & 15, r4 = lane >> 4;
+  if constexpr (has_aux) {
+#pragma unroll 1
+    for (int t0 = 0; t0 < 32; t0 += 8) {      // eight loads in flight
+      uint4 v[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        v[t] = load_stream<NT>(p.aux + (size_t)(row0 + 4 * (t0 + t) + r4) * p.ldaux + col0 + 8 * c16);
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        *reinterpret_cast<uint4*>(patch + (4 * (t0 + t) + r4) * kW4PatchPitch + 16 * c16) = v[t];
+    }
+  }
+  float bias[8][4];
+  if constexpr (EPI != EPI_STORE) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint2 b = *reinterpret_cast<const uint2*>(p.bias + col0 + 16 * j + 4 * q);
+      bias[j][0] = __uint_as_float(b.x << 16); bias[j][1] = __uint_as_float(b.x & 0xFFFF0000u);
+      bias[j][2] = __uint_as_float(b.y << 16); bias[j][3] = __uint_as_float(b.y & 0xFFFF0000u);
+    }
+  }
+  char* cell0 = patch + l16 * kW4PatchPitch + 8 * q;      // block (i, j): + 16 i rows + 32 j bytes
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      char* cell = cell0 + 16 * i * kW4PatchPitch + 32 * j;
+      float x[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[r] = acc_read(acc.blk[i][j][r]);
+      if constexpr (has_aux) {
+        const uint2 a = *reinterpret_cast<const uint2*>(cell);
+        const float av[4] = {__uint_as_float(a.x << 16), __uint_as_float(a.x & 0xFFFF0000u),
+                             __uint_as_float(a.y << 16), __uint_as_float(a.y & 0xFFFF0000u)};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = x[r] + bias[j][r] + av[r];
+      } else if constexpr (EPI == EPI_BIAS) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] += bias[j][r];
+      }
+      *reinterpret_cast<uint2*>(cell) = make_uint2(cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3]));
+      if (j == 7) __builtin_amdgcn_sched_barrier(0);     // a block row at a time: few registers
+    }
+  bf16_raw* C = reinterpret_cast<bf16_raw*>(p.C);
+#pragma unroll 1
+  for (int t0 = 0; t0 < 32; t0 += 8)
+#pragma unroll
+    for (int tt = 0; tt < 8; ++tt) {
+      const int row = 4 * (t0 + tt) + r4;
+      const uint4 v = *reinterpret_cast<const uint4*>(patch + row * kW4PatchPitch + 16 * c16);
+      const int col = col0 + 8 * c16;
+      if constexpr (EPI == EPI_BIAS_RESID_ENCODE) {
+        // the 8 lanes of a row segment hold one 64-element block of the bf16 values that a plain store would write
+        float x[8];
+        unpack8(v, x);
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(x[e]));
+        amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+        const float sc = block_scale_rounded(amax / 127.0f, p.scales16);
+        uint32_t w[2] = {0u, 0u};
+        if (sc != 0.0f) {
+          const BlockDivisor div(sc);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float qv = fminf(fmaxf(rintf(div.quotient(x[e])), -127.0f), 127.0f);
+            w[e >> 2] |= ((uint32_t)(int)qv & 0xFFu) << (8 * (e & 3));
+          }
+        }
+        const size_t e0 = (size_t)(row0 + row) * p.ldc + col;
+        *reinterpret_cast<uint2*>(reinterpret_cast<int8_t*>(p.C) + e0) = make_uint2(w[0], w[1]);
+        if ((c16 & 7) == 0) block_scale_store(p.scales, e0 >> 6, sc, p.scales16);
+      } else {
+        store_stream<NT>(C + (size_t)(row0 + row) * p.ldc + col, v);
+      }
+    }
+}
+
+// one uniform branch per epilogue kind and store kind: every copy is straight-line code
+__device__ __forceinline__ void w4_epilogue(const KArgs& p, const Acc16<4, 4>& acc, int row0, int col0, int lane,
+                                            char* patch) {
+  const int epi = p.epilogue;
+  if (epi == EPI_PART_F32) return w4_epilogue_nt<EPI_PART_F32, false>(p, acc, row0, col0, lane, patch);
+  if (p.stream) {
+    if (epi == EPI_STORE) return w4_epilogue_nt<EPI_STORE, true>(p, acc, row0, col0, lane, patch);
+    if (epi == EPI_BIAS) return w4_epilogue_nt<EPI_BIAS, true>(p, acc, row0, col0, lane, patch);
+    if (epi == EPI_BIAS_RESID) return w4_epilogue_nt<EPI_BIAS_RESID, true>(p, acc, row0, col0, lane, patch);
+    return w4_epilogue_nt<EPI_BIAS_RESID_ENCODE, true>(p, acc, row0, col0, lane, patch);
+  }
+  if (epi == EPI_STORE) return w4_epilogue_nt<EPI_STORE, false>(p, acc, row0, col0, lane, patch);
+  if (epi == EPI_BIAS) return w4_epilogue_nt<EPI_BIAS, false>(p, acc, row0, col0, lane, patch);
+  if (epi == EPI_BIAS_RESID) return w4_epilogue_nt<EPI_BIAS_RESID, false>(p, acc, row0, col0, lane, patch);
+  return w4_epilogue_nt<EPI_BIAS_RESID_ENCODE, false>(p, acc, row0, col0, lane, patch);
+}
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(KArgs p) {
+  constexpr int NW = 4, WN = 2;
+  constexpr int WTM = BM / 2, WTN = BN / 2;
+  constexpr int FM = WTM / 16, FN = WTN / 16;
+  constexpr int STAGE = (BM + BN) * DBK;              // elements
+  constexpr int IPW = (BM + BN) * DBK / 512 / NW;       // load instructions per wavefront per stage
+  constexpr int IPA = BM * DBK / 512 / NW;
+  constexpr int NR = FM + FN;                           // fragment reads per sub-step
+  static_assert(DBK == 64 && NS == 2, "two 32-deep sub-steps per slice, two stages");
+  static_assert(2 * NR + 2 <= FM * FN && 4 * IPW <= FM * FN, "read / load slots of a sub-step");
+  extern __shared__ __attribute__((aligned(1024))) bf16_raw lds[];
+#ifdef SWARM_KERNEL_HOOKS
+  long long stamp[4], cyc[2];
+  stamp[0] = wall_clock64();
+#endif
+
+  int tile_m, tile_n;
+  if (p.ksplit > 1) {
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int part = blockIdx.x / ntiles;
+    tile_of_block(p, tile_m, tile_n, blockIdx.x - part * ntiles);
+    p.K /= p.ksplit;
+    p.A += (size_t)part * p.K;
+    p.B += (size_t)part * p.K;
+    p.C = p.part + (size_t)part * p.M * p.N;
+    p.ldc = p.N;
+    p.epilogue = EPI_PART_F32;
+  } else {
+    tile_of_block(p, tile_m, tile_n);
+  }
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int l16 = lane & 15, q = lane >> 4;
+
+  Acc16<WTM / 32, WTN / 32> acc;
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc.blk[i][j][r] = 0.f;
+
+  const int KT = p.K / DBK;
+  issue_tile<BM, NW, false, true>(p.A, p.lda, m0, 0, lds, wave, lane);
+  issue_tile<BN, NW, false, true>(p.B, p.ldb, n0, 0, lds + BM * DBK, wave, lane);
+  {
+    const int k1 = min(1, KT - 1) * DBK;
+    issue_tile<BM, NW, false, true>(p.A, p.lda, m0, k1, lds + STAGE, wave, lane);
+    issue_tile<BN, NW, false, true>(p.B, p.ldb, n0, k1, lds + STAGE + BM * DBK, wave, lane);
+  }
+  wait_vmcnt<IPW>();
+  __builtin_amdgcn_s_barrier();
+#ifdef SWARM_KERNEL_HOOKS
+  stamp[1] = wall_clock64();
+  cyc[0] = clock64();
+#endif
+
+  // byte address of this lane's 16 bytes of fragment 0 of A resp. B in stage 0, sub-step kk (fragment i adds
+  // 16 rows = 2048 bytes as an immediate; the chunk swizzle depends on the row's low bits only)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds;
+  uint32_t offA[2], offB[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const uint32_t chunk = (uint32_t)((4 * kk + q) ^ swz_rows16(l16)) * 16u;
+    offA[kk] = lds0 + (uint32_t)(wm * WTM + l16) * (DBK * 2) + chunk;
+    offB[kk] = lds0 + (uint32_t)(BM + wn * WTN + l16) * (DBK * 2) + chunk;
+  }
+  bf16x8 fa[2][FM], fb[2][FN];
+  static_for<FM>([&](auto ic) __attribute__((always_inline)) {
+    fa[0][decltype(ic)::value] = lds_frag_plain<2048 * decltype(ic)::value>(offA[0]);
+  });
+  static_for<FN>([&](auto jc) __attribute__((always_inline)) {
+    fb[0][decltype(jc)::value] = lds_frag_plain<2048 * decltype(jc)::value>(offB[0]);
+  });
+
+  // One sub-step: FM * FN MFMAs on buffer CUR; the fragments of the next sub-step (stage byte offset nst, sub-step
+  // nkk) go into the other buffer behind the even MFMAs 2 r.  KIND 1: wait and barrier behind MFMA 1, the reads start
+  // behind MFMA 2, and the loads of slice lk go into stage ls behind the MFMAs 4 t + 3.
+  auto substep = [&](auto kind_c, auto cur_c, uint32_t nst, int nkk, int lk, int ls) __attribute__((always_inline)) {
+    constexpr int KIND = decltype(kind_c)::value;
+    constexpr int CUR = decltype(cur_c)::value, NXT = 1 - CUR;
+    constexpr int R0 = KIND == 1 ? 2 : 0;     // MFMA slot of the first read
+    bf16_raw* st = lds + ls * STAGE;
+    const uint32_t na = offA[nkk] + nst, nb = offB[nkk] + nst;
+    static_for<FM * FN>([&](auto nc) __attribute__((always_inline)) {
+      constexpr int n = decltype(nc)::value;
+      constexpr int i = n / FN;
+      constexpr int j = (i & 1) ? FN - 1 - n % FN : n % FN;    // rows alternate direction: one operand changes per MFMA
+      if constexpr (n == 0) {
+        // buffer CUR was requested during the first half of the previous sub-step
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (KIND == 1 && n == 2) {
+        // slice kt+1 has landed (this wavefront's part), this wavefront's reads of slice kt are complete: all meet
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // B fragment first: the block comes out with the lane's four registers along a row of C (see w4_epilogue_nt)
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc.blk[i][j]) : "v"(fb[CUR][j]), "v"(fa[CUR][i]));
+      if constexpr (n >= R0 && (n - R0) % 2 == 0 && (n - R0) / 2 < NR) {
+        constexpr int r = (n - R0) / 2;
+        if constexpr (r < FN) fb[NXT][r < FN ? r : 0] = lds_frag_plain<2048 * (r < FN ? r : 0)>(nb);
+        else fa[NXT][r >= FN ? r - FN : 0] = lds_frag_plain<2048 * (r >= FN ? r - FN : 0)>(na);
+      }
+      if constexpr (KIND == 1 && n % 4 == 3 && n / 4 < IPW) {
+        constexpr int t = n / 4;
+        if constexpr (t < IPA) issue_tile_one<BM, NW, false, true>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+        else issue_tile_one<BN, NW, false, true>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  for (int kt = 0; kt < KT; ++kt) {
+    const uint32_t cst = (uint32_t)(kt & 1) * (STAGE * 2), nst = (uint32_t)((kt + 1) & 1) * (STAGE * 2);
+    substep(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, cst, 1, 0, 0);
+    // the stage of slice kt is free behind the barrier (the last iterations re-fetch the last slice instead of
+    // branching)
+    substep(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, nst, 0, min(kt + 2, KT - 1), kt & 1);
+  }
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_s_barrier();   // every wavefront is past its last LDS read: the stages become epilogue patches
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last in-place MFMAs retire before their results are read
+#ifdef SWARM_KERNEL_HOOKS
+  stamp[2] = wall_clock64();
+  cyc[1] = clock64();
+#endif
+
+  static_assert(WTM == 128 && WTN == 128, "the epilogue's patch is 128 x 128");
+  char* patch = reinterpret_cast<char*>(lds) + wave * kW4PatchBytes;
+  w4_epilogue(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane, patch);
+#ifdef SWARM_KERNEL_HOOKS
+  if (p.stamps) {
+    wait_vmcnt<0>();   // the stores have left
+    stamp[3] = wall_clock64();
+    if (threadIdx.x == 0) {
+      long long* out = p.stamps + (size_t)blockIdx.x * 16;
+      out[0] = stamp[0]; out[1] = stamp[1]; out[2] = stamp[2]; out[3] = stamp[3];
+      out[4] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));    // HW_ID: compute unit, shader engine
+      out[5] = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11));   // XCC_ID
+      out[6] = tile_m; out[7] = tile_n;
+      out[8] = cyc[1] - cyc[0];   // shader cycles spent in the loop
+    }
+  }
+#endif
+}
+
+#ifdef SWARM_KERNEL_HOOKS
+int g_gemm_four_waves = 1;   // measurement switch of the instrumented build (swarm_kernel_gemm_four_waves)
+#endif
+
+swarm_status launch_w4(const KArgs& k, hipStream_t st) {
+  constexpr size_t stage_bytes = (size_t)NS * 512 * DBK * sizeof(bf16_raw);
+  constexpr size_t lds_bytes = stage_bytes > 4 * (size_t)kW4PatchBytes ? stage_bytes : 4 * (size_t)kW4PatchBytes;
+  void (*kern)(KArgs) = gemm_bf16_w4_kernel<256, 256>;
+  static LdsOptIn opted;
+  if (lds_opt_in((const void*)kern, lds_bytes, opted) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3(k.tiles_m * k.tiles_n * (k.ksplit > 1 ? k.ksplit : 1)), dim3(256), lds_bytes, st, k);
+  return launch_status();
+}
+
 template <int BM, int BN, int WM, int WN, bool A_T, bool B_T>
 swarm_status launch_dma(const KArgs& k, hipStream_t st) {
   constexpr size_t lds_bytes = (size_t)NS * (BM + BN) * DBK * sizeof(bf16_raw);
@@ -527,6 +856,15 @@ swarm_status launch_dma(const KArgs& k, hipStream_t st) {
 
 template <int BM, int BN, int WM, int WN>
 swarm_status launch_dma_layout(const KArgs& k, bool a_t, bool b_t, hipStream_t st) {
+  if constexpr (BM == 256 && BN == 256) {
+    // both operands k-contiguous and a short epilogue: four wavefronts of 128 x 128.  The epilogues with much
+    // vector arithmetic (GeLU, rotary, GeGLU) stay on eight wavefronts: two per SIMD issue it twice as fast.
+    bool w4 = !a_t && !b_t && w4_epilogue_ok(k.epilogue);
+#ifdef SWARM_KERNEL_HOOKS
+    w4 = w4 && g_gemm_four_waves;
+#endif
+    if (w4) return launch_w4(k, st);
+  }
   if (!a_t && !b_t) return launch_dma<BM, BN, WM, WN, false, false>(k, st);
   if (!a_t && b_t) return launch_dma<BM, BN, WM, WN, false, true>(k, st);
   if (a_t && b_t) return launch_dma<BM, BN, WM, WN, true, true>(k, st);
@@ -696,3 +1034,8 @@ swarm_status gemm_bf16_dma(const GemmArgs& g, hipStream_t st) {
 }
 
 }  // namespace swarm
+
+#ifdef SWARM_KERNEL_HOOKS
+// instrumented build: 0 = forward products on the eight-wavefront kernel as well (for A/B measurements)
+extern "C" void swarm_kernel_gemm_four_waves(int on) { swarm::g_gemm_four_waves = on; }
+#endif
