@@ -545,7 +545,8 @@ constexpr int kW4PatchPitch = 272;                       // bytes per patch row:
 constexpr int kW4PatchBytes = 128 * kW4PatchPitch;       // per wavefront
 
 inline bool w4_epilogue_ok(int epi) {
-  return epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_RESID_ENCODE;
+  return epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_RESID_ENCODE ||
+         epi == EPI_BIAS_GELU;
 }
 
 // one accumulator register into a vector register, where it is used (left to itself the compiler moves all 256
@@ -598,6 +599,31 @@ __device__ __forceinline__ void w4_epilogue_nt(const KArgs& p, const Acc16<4, 4>
     }
   }
   char* cell0 = patch + l16 * kW4PatchPitch + 8 * q;      // block (i, j): + 16 i rows + 32 j bytes
+  if constexpr (EPI == EPI_BIAS_GELU) {
+    // two outputs, two passes through the patch: the pre-activations u = acc + bias (when the caller keeps them),
+    // then gelu(u) of the same fp32 values
+    if (p.C2) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          float x[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) x[r] = acc_read(acc.blk[i][j][r]) + bias[j][r];
+          *reinterpret_cast<uint2*>(cell0 + 16 * i * kW4PatchPitch + 32 * j) =
+              make_uint2(cvt_pk_bf16(x[0], x[1]), cvt_pk_bf16(x[2], x[3]));
+          if (j == 7) __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll 1
+      for (int t0 = 0; t0 < 32; t0 += 8)
+#pragma unroll
+        for (int tt = 0; tt < 8; ++tt) {
+          const int row = 4 * (t0 + tt) + r4;
+          const uint4 v = *reinterpret_cast<const uint4*>(patch + row * kW4PatchPitch + 16 * c16);
+          store_stream<NT>(p.C2 + (size_t)(row0 + row) * p.ldc2 + col0 + 8 * c16, v);
+        }
+    }
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
@@ -606,7 +632,10 @@ __device__ __forceinline__ void w4_epilogue_nt(const KArgs& p, const Acc16<4, 4>
       float x[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[r] = acc_read(acc.blk[i][j][r]);
-      if constexpr (has_aux) {
+      if constexpr (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = gelu_fast(x[r] + bias[j][r]);
+      } else if constexpr (has_aux) {
         const uint2 a = *reinterpret_cast<const uint2*>(cell);
         const float av[4] = {__uint_as_float(a.x << 16), __uint_as_float(a.x & 0xFFFF0000u),
                              __uint_as_float(a.y << 16), __uint_as_float(a.y & 0xFFFF0000u)};
@@ -665,11 +694,13 @@ __device__ __forceinline__ void w4_epilogue(const KArgs& p, const Acc16<4, 4>& a
     if (epi == EPI_STORE) return w4_epilogue_nt<EPI_STORE, true>(p, acc, row0, col0, lane, patch);
     if (epi == EPI_BIAS) return w4_epilogue_nt<EPI_BIAS, true>(p, acc, row0, col0, lane, patch);
     if (epi == EPI_BIAS_RESID) return w4_epilogue_nt<EPI_BIAS_RESID, true>(p, acc, row0, col0, lane, patch);
+    if (epi == EPI_BIAS_GELU) return w4_epilogue_nt<EPI_BIAS_GELU, true>(p, acc, row0, col0, lane, patch);
     return w4_epilogue_nt<EPI_BIAS_RESID_ENCODE, true>(p, acc, row0, col0, lane, patch);
   }
   if (epi == EPI_STORE) return w4_epilogue_nt<EPI_STORE, false>(p, acc, row0, col0, lane, patch);
   if (epi == EPI_BIAS) return w4_epilogue_nt<EPI_BIAS, false>(p, acc, row0, col0, lane, patch);
   if (epi == EPI_BIAS_RESID) return w4_epilogue_nt<EPI_BIAS_RESID, false>(p, acc, row0, col0, lane, patch);
+  if (epi == EPI_BIAS_GELU) return w4_epilogue_nt<EPI_BIAS_GELU, false>(p, acc, row0, col0, lane, patch);
   return w4_epilogue_nt<EPI_BIAS_RESID_ENCODE, false>(p, acc, row0, col0, lane, patch);
 }
 

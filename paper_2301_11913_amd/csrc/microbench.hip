@@ -123,10 +123,46 @@ __global__ __launch_bounds__(512) void lds_read_kernel(float* __restrict__ sink,
   sink[(size_t)blockIdx.x * 512 + threadIdx.x] = __uint_as_float((x0 ^ x1 ^ x2 ^ x3) & 0x3FFFFFFFu);
 }
 
+// Vector-arithmetic rate of ONE workgroup per compute unit (96 KiB of LDS requested, so no second one fits) of
+// THREADS / 64 wavefronts: every lane runs `iters` rounds of the GEMM epilogue's GeLU on 8 independent values.
+// 256 threads = one wavefront per SIMD, 512 = two.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void valu_rate_kernel(const float* __restrict__ in, float* __restrict__ sink,
+                                                             int iters, long long* __restrict__ clocks) {
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = in[(threadIdx.x * 8 + e) & 4095];
+  stamp_clocks(clocks, false);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = gelu_fast(x[e]) + 0.25f;
+  }
+  stamp_clocks(clocks, true);
+  float t = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) t += x[e];
+  sink[(size_t)blockIdx.x * THREADS + threadIdx.x] = t;
+}
+
 }  // namespace
 }  // namespace swarm
 
 using namespace swarm;
+
+// in: 4096 floats; sink: workgroups x 512 floats; clocks: workgroups x 4 int64.  waves_per_simd: 1 or 2.
+extern "C" int swarm_microbench_valu_rate(int waves_per_simd, const float* in, float* sink, long long* clocks, int iters,
+                                          int workgroups, void* stream) {
+  if (!in || !sink || !clocks || iters < 1 || workgroups < 1 || (waves_per_simd != 1 && waves_per_simd != 2))
+    return SWARM_ERR_SHAPE;
+  static LdsOptIn opted[2];
+  const void* k = waves_per_simd == 1 ? (const void*)valu_rate_kernel<256> : (const void*)valu_rate_kernel<512>;
+  if (lds_opt_in(k, 98304, opted[waves_per_simd - 1]) != SWARM_OK) return SWARM_ERR_LAUNCH;
+  if (waves_per_simd == 1)
+    hipLaunchKernelGGL(valu_rate_kernel<256>, dim3(workgroups), dim3(256), 98304, (hipStream_t)stream, in, sink, iters, clocks);
+  else
+    hipLaunchKernelGGL(valu_rate_kernel<512>, dim3(workgroups), dim3(512), 98304, (hipStream_t)stream, in, sink, iters, clocks);
+  return launch_status();
+}
 
 // operands: 8 x 12 x 64 uint4 (device); sink: workgroups x 512 floats; clocks: workgroups x 4 int64.
 // Launches the loop once on `stream`; the caller times it.  shape 0: 16 x 16 x 32 (32 MFMAs per iteration and

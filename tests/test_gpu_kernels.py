@@ -173,6 +173,52 @@ def test_gemm_streaming_outputs(epi, b_t):
     gemm_case(8192, 4096, 128, False, b_t, epi, seed=70 + epi)
 
 
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 6])
+@pytest.mark.parametrize("shape", [(4096, 4096, 192), (8192, 4096, 128), (2560, 4096, 64)])
+def test_gemm_four_wavefront_kernel_same_bits(epi, shape):
+    """Forward products on 256 x 256 tiles run on four wavefronts of 128 x 128 (accumulators in place, epilogue on
+    the accumulator layout); the instrumented library can send them to the eight-wavefront kernel instead.  Both
+    accumulate in the same order and round once, so every output (C, the kept pre-activations, int8 codes and
+    scales) has to agree bit for bit; 160, 256 and 512 tiles, cached and streaming stores, one to three slices."""
+    M, N, K = shape
+    lib = _lib()
+    lib.swarm_kernel_gemm_ws.restype = C.c_int
+    lib.swarm_kernel_gemm_ws.argtypes = [C.c_int] * 3 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                                        C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_int,
+                                                        C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    A = _bf(synth.normal(90 + epi, "A", (M, K))).cuda(); B = _bf(synth.normal(90 + epi, "B", (N, K))).cuda()
+    bias = _bf(synth.normal(90 + epi, "bias", (N,))).cuda(); aux = _bf(synth.normal(90 + epi, "aux", (M, N))).cuda()
+    outs = []
+    for four in (1, 0):
+        lib.swarm_kernel_gemm_four_waves(four)
+        try:
+            if epi == 6:
+                Cd = torch.zeros((M, N), dtype=torch.int8, device="cuda")
+                sc = torch.zeros(M * N // 64, dtype=torch.float32, device="cuda")
+                st = lib.swarm_kernel_gemm_ws(M, N, K, A.data_ptr(), K, 0, B.data_ptr(), K, 0, Cd.data_ptr(), N, 6,
+                                              bias.data_ptr(), aux.data_ptr(), N, sc.data_ptr(), None, 0, None)
+                assert st == 0
+                outs.append((Cd, sc.view(torch.int32)))
+            else:
+                res = []
+                for keep_u in ((True, False) if epi == 3 else (False,)):
+                    Cd = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
+                    C2 = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda") if keep_u else None
+                    st = lib.swarm_kernel_gemm(1, M, N, K, A.data_ptr(), K, 0, B.data_ptr(), K, 0, Cd.data_ptr(), N, epi,
+                                               bias.data_ptr(), aux.data_ptr(), N,
+                                               C2.data_ptr() if keep_u else None, N, None)
+                    assert st == 0
+                    res += [Cd.view(torch.int16)] + ([C2.view(torch.int16)] if keep_u else [])
+                outs.append(tuple(res))
+        finally:
+            lib.swarm_kernel_gemm_four_waves(1)
+    torch.cuda.synchronize()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    if epi == 3:      # with and without the kept pre-activations: the same GeLU values
+        assert torch.equal(outs[0][0], outs[0][2])
+
+
 def test_gemm_splitk_encode_equals_encode_of_stored():
     """EPI 6 (bias + residual, int8-encoded) through the split path: codes and scales are those of the stand-alone
     codec applied to what the bias + residual epilogue stores (same scratch, same summation order)."""
