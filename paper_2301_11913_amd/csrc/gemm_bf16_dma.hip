@@ -90,6 +90,49 @@ __device__ __forceinline__ void issue_tile_one(const bf16_raw* __restrict__ g, i
   }
 }
 
+// The same load with its address split into a wave-uniform 64-bit base (tile origin, slice, instruction index:
+// scalar arithmetic) and ONE 32-bit per-lane byte offset that is computed once per kernel.  issue_tile_one forms
+// the whole 64-bit address per lane and instruction, and for an operand whose rows are `ld` apart the compiler
+// re-multiplies by ld inside the loop (two v_mul_lo_u32 and a v_mad_u64_u32 per load, all quarter rate) rather
+// than keep 16 address registers; here a load costs a few scalar instructions.
+//   rows as tile rows   : lane offset = ((wave * 8 + lane / 8) * ld + chunk * 8) * 2,
+//                         base(t) = g + ((r0 + t * NW * 8) * ld + k0) * 2
+//   k-rows as tile rows : lane offset = ((wave * RPI + lane / CPR) * ld + chunk * 8) * 2,
+//                         base(t) = g + ((k0 + t * NW * RPI) * ld + r0) * 2          (RPI = 64 / CPR k-rows per load)
+// The chunk swizzle is the one of issue_tile_one; it does not depend on t except for (TRANS, K32, BR = 256, NW = 4),
+// where it alternates with t (off[t & 1]).
+template <int BR, int NW, bool TRANS, bool K32>
+struct TileLoad {
+  static constexpr bool ALT = TRANS && K32 && BR == 256 && NW == 4;
+  uint32_t off[ALT ? 2 : 1];
+  __device__ __forceinline__ void init(int ld, int wave, int lane) {
+#pragma unroll
+    for (int a = 0; a < (ALT ? 2 : 1); ++a) {
+      const int q = wave + a * NW;
+      if constexpr (!TRANS) {
+        const int row = q * (64 / KCH) + lane / KCH;
+        const int chunk = (lane % KCH) ^ swz_rows_of<K32>(row);
+        off[a] = (uint32_t)((wave * (64 / KCH) + lane / KCH) * ld + chunk * 8) * 2u;
+      } else {
+        constexpr int CPR = BR / 8;
+        const int krow = q * (64 / CPR) + lane / CPR;
+        const int chunk = (lane % CPR) ^ (4 * (krow & 3)) ^ (K32 ? 2 * ((krow >> 3) & 1) : 0);
+        off[a] = (uint32_t)((wave * (64 / CPR) + lane / CPR) * ld + chunk * 8) * 2u;
+      }
+    }
+  }
+  // the t-th of this wavefront's loads of the tile (r0, k0) into the stage at `lds`
+  __device__ __forceinline__ void issue(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
+                                        int wave, int t) const {
+    const int q = wave + t * NW;
+    size_t base;
+    if constexpr (!TRANS) base = ((size_t)(r0 + t * NW * (64 / KCH)) * ld + k0) * 2;
+    else base = ((size_t)(k0 + t * NW * (64 / (BR / 8))) * ld + r0) * 2;
+    const char* src = reinterpret_cast<const char*>(g) + base + off[ALT ? (t & 1) : 0];
+    __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(lds + q * 512), 16, 0, 0);
+  }
+};
+
 template <int BR, int NW, bool TRANS, bool K32 = false>
 __device__ __forceinline__ void issue_tile(const bf16_raw* __restrict__ g, int ld, int r0, int k0, bf16_raw* lds,
                                            int wave, int lane, int glu_split = 0) {
@@ -244,6 +287,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
   };
   // multiply (ca, cb); read the fragments of sub-step nkk of the tile at nA into (na, nb); with LOADS, issue the
   // loads of slice `lk` into stage `ls`
+  // loads inside the loop: split addresses where an operand is transposed (see TileLoad)
+  constexpr bool SPLIT_ADDR = A_T || B_T;
+  TileLoad<BM, NW, A_T, false> ldA;
+  TileLoad<BN, NW, B_T, false> ldB;
+  if constexpr (SPLIT_ADDR) {
+    ldA.init(p.lda, wave, lane);
+    ldB.init(p.ldb, wave, lane);
+  }
   auto substep = [&](const bf16x8 (&ca)[FM], const bf16x8 (&cb)[FN], const bf16_raw* nA, int nkk, bf16x8 (&na)[FM],
                      bf16x8 (&nb)[FN], bool loads, int lk, int ls) {
     bf16_raw* st = lds + ls * STAGE;
@@ -257,8 +308,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_dma_kernel(KArgs p) {
       if (loads) {
 #pragma unroll
         for (int t = n * LPM; t < (n + 1) * LPM && t < IPW; ++t) {
-          if (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
-          else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+          if constexpr (SPLIT_ADDR) {
+            if (t < IPA) ldA.issue(p.A, p.lda, m0, lk * DBK, st, wave, t);
+            else ldB.issue(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, t - IPA);
+          } else {
+            if (t < IPA) issue_tile_one<BM, NW, A_T>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+            else issue_tile_one<BN, NW, B_T>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -440,6 +496,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
   for (int j = 0; j < FN; ++j) fb[0][j] = read_b(lds, j, 0);
   lds_reads_done();
 
+  // loads inside the loop: split addresses where an operand is transposed (the k-contiguous forward layout keeps
+  // issue_tile_one, which also knows the GeGLU row gather)
+  constexpr bool SPLIT_ADDR = A_T || B_T;
+  TileLoad<BM, NW, A_T, true> ldA;
+  TileLoad<BN, NW, B_T, true> ldB;
+  if constexpr (SPLIT_ADDR) {
+    ldA.init(p.lda, wave, lane);
+    ldB.init(p.ldb, wave, lane);
+  }
   constexpr int IA = A_T ? 2 : 1, IB = B_T ? 2 : 1;
   // One sub-step: FM * FN MFMAs on (fa, cb); behind them the reads of the next sub-step's fragments from the tile
   // at nA, sub-step nkk (A in place, B into nb).  KIND 1: the per-slice wait and barrier sit behind the first row,
@@ -470,8 +535,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_k32_kernel(KArgs p) {
       if constexpr (f >= FM) nb[f - FM] = read_b(nA, f - FM, nkk);
       if constexpr (KIND == 1 && n >= FN + 2 && (n - FN) % 2 == 0 && (n - FN - 2) / 2 < IPW) {
         constexpr int t = (n - FN - 2) / 2;
-        if constexpr (t < IPA) issue_tile_one<BM, NW, A_T, true>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
-        else issue_tile_one<BN, NW, B_T, true>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+        if constexpr (SPLIT_ADDR) {
+          if constexpr (t < IPA) ldA.issue(p.A, p.lda, m0, lk * DBK, st, wave, t);
+          else ldB.issue(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, t - IPA);
+        } else {
+          if constexpr (t < IPA) issue_tile_one<BM, NW, A_T, true>(p.A, p.lda, m0, lk * DBK, st, wave, lane, t);
+          else issue_tile_one<BN, NW, B_T, true>(p.B, p.ldb, n0, lk * DBK, st + BM * DBK, wave, lane, t - IPA, glu);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     });
