@@ -106,7 +106,8 @@ def gemm_roofline(step, steps, ms_per_step, workload):
                       "epilogue": EPI_NAMES.get(epi, str(epi)), "launches_per_step": cnt // steps,
                       "avg_us": round(ms * 1e3 / cnt, 1), "TFLOP/s": round(tf, 1),
                       "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 3)})
-    out = {"bound": "mfma", "kernel": "gemm_bf16_k32_kernel", "achieved": round(achieved, 1),
+    out = {"bound": "mfma", "kernel": "gemm_bf16_w4_kernel (forward products) + gemm_bf16_k32_kernel (dgrad, wgrad)",
+           "achieved": round(achieved, 1),
            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
            "traffic": measured_traffic(workload), "launches_per_step": launches // steps,
            "avg_launch_us": round(tot_ms * 1e3 / launches, 1), "flops_per_launch": tot_fl / launches,

@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Micro-benchmarks behind the roofline discussion of the bf16 MFMA GEMM (one MI355X).
 
-    python bench_micro.py [--what mfma,lds,stamps,data,vendor] [--json PATH]
+    python bench_micro.py [--what mfma,lds,valu,stamps,data,vendor] [--json PATH]
 
   mfma   : a loop of nothing but MFMAs on register operands, in the GEMM kernel's shape (8 wavefronts per workgroup,
            two per SIMD, 128 accumulator registers per lane), for both bf16 MFMA shapes and for constant and random
            operand bits; reports TFLOP/s and the clock the chip ran at (shader-cycle counter over the 100 MHz wall clock)
   lds    : a loop of nothing but LDS fragment reads in the GEMM kernel's two read shapes and swizzles (bytes per clock
            and compute unit)
+  valu   : the GEMM epilogue's GeLU on register values, one workgroup per compute unit, with one and with two
+           wavefronts per SIMD: what a lone wavefront per SIMD (the four-wavefront GEMM kernel) can issue
   stamps : the 256 x 256 GEMM kernel of the instrumented build with wall-clock stamps at four points of every workgroup
            (first loads | loop | epilogue | gap to the next workgroup on the same compute unit), on the three layouts
            at the config-5 shapes
@@ -124,6 +126,35 @@ def run_lds(lib, out):
           "wavefronts = 1024 cycles at full rate: 96 B/clk.\n")
 
 
+def run_valu(lib, out):
+    lib.swarm_microbench_valu_rate.restype = C.c_int
+    lib.swarm_microbench_valu_rate.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    inp = torch.randn(4096, device="cuda")
+    wgs, iters = 1024, 2000
+    sink = torch.empty(wgs * 512, device="cuda")
+    clocks = torch.zeros(wgs * 4, dtype=torch.int64, device="cuda")
+    rows = []
+    for w in (1, 2, 1, 2):
+        call = lambda: lib.swarm_microbench_valu_rate(w, inp.data_ptr(), sink.data_ptr(), clocks.data_ptr(), iters, wgs, None)
+        for _ in range(2):
+            assert call() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); assert call() == 0; e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        ghz, _ = _clock_ghz(clocks)
+        rows.append({"wavefronts_per_simd": w, "ms": round(ms, 3), "G_gelu_per_s": round(wgs * w * 256 * 8 * iters / ms / 1e6, 1),
+                     "shader_clock_GHz": round(ghz, 3)})
+    out["valu"] = rows
+    print("## Vector arithmetic (the epilogue's GeLU on 8 register values per lane), one workgroup per compute unit\n")
+    print("| wavefronts per SIMD | ms | 10^9 GeLU / s over the chip | shader clock (GHz) |")
+    print("|---|---|---|---|")
+    for r in rows:
+        print("| %d | %.3f | %.1f | %.3f |" % (r["wavefronts_per_simd"], r["ms"], r["G_gelu_per_s"], r["shader_clock_GHz"]))
+    print()
+
+
 def run_stamps(lib, out):
     lib.swarm_kernel_gemm_stamped.restype = C.c_int
     lib.swarm_kernel_gemm_stamped.argtypes = [C.c_int] * 3 + [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
@@ -131,14 +162,19 @@ def run_stamps(lib, out):
                                                             C.c_void_p, C.c_void_p]
     rows = []
     print("## Phases of a 256 x 256 tile (wall-clock stamps in every workgroup, microseconds, mean over the tiles)\n")
-    print("| product (M x N x K, layout, epilogue) | kernel | first loads | loop (p10 - p90) | epilogue | gap to next workgroup | "
-          "loop alone TFLOP/s | launch TFLOP/s | loop time by XCD (min - max) | last tile ends after first idle CU |\n"
-          "|---|---|---|---|---|---|---|---|---|---|")
-    for (M, N, K, a_t, b_t, epi, label) in ((8192, 12288, 4096, 0, 0, 1, "forward, bias"),
-                                           (8192, 16384, 4096, 0, 0, 3, "forward, bias + GeLU"),
-                                           (8192, 16384, 4096, 0, 1, 4, "dgrad, x GeLU'"),
-                                           (8192, 4096, 16384, 0, 0, 2, "forward, bias + residual"),
-                                           (16384, 4096, 8192, 1, 1, 5, "wgrad, fp32 +=")):
+    print("| product (M x N x K, layout, epilogue; wavefronts per tile) | kernel | first loads | loop (p10 - p90) | epilogue | "
+          "gap to next workgroup | loop alone TFLOP/s | launch TFLOP/s | loop time by XCD (min - max) | "
+          "last tile ends after first idle CU |\n|---|---|---|---|---|---|---|---|---|---|")
+    # forward products run on the four-wavefront kernel; the instrumented library can send them to the
+    # eight-wavefront one (same tile, same epilogue arithmetic), measured here beside it
+    for (M, N, K, a_t, b_t, epi, label, four) in (
+            (8192, 12288, 4096, 0, 0, 1, "forward, bias; 4", 1), (8192, 12288, 4096, 0, 0, 1, "forward, bias; 8", 0),
+            (8192, 16384, 4096, 0, 0, 3, "forward, bias + GeLU; 4", 1), (8192, 16384, 4096, 0, 0, 3, "forward, bias + GeLU; 8", 0),
+            (8192, 4096, 16384, 0, 0, 2, "forward, bias + residual; 4", 1),
+            (8192, 4096, 16384, 0, 0, 2, "forward, bias + residual; 8", 0),
+            (8192, 16384, 4096, 0, 1, 4, "dgrad, x GeLU'; 8", 1), (8192, 4096, 16384, 0, 1, 0, "dgrad, store; 8", 1),
+            (16384, 4096, 8192, 1, 1, 5, "wgrad, fp32 +=; 8", 1)):
+        lib.swarm_kernel_gemm_four_waves(four)
         g = torch.Generator(device="cuda"); g.manual_seed(M + K)
         rn = lambda *s: torch.randn(*s, generator=g, device="cuda").to(torch.bfloat16)
         A = rn(K, M) if a_t else rn(M, K)
@@ -188,6 +224,7 @@ def run_stamps(lib, out):
             "%.2f" % r["gap_us"] if r["gap_us"] is not None else "-", r["loop_TFLOPs"], r["launch_TFLOPs"], *r["loop_by_xcd"],
             r["end_spread_us"]))
         del A, B, Cd, aux
+    lib.swarm_kernel_gemm_four_waves(1)
     out["tile_phases"] = rows
     print("\nPer XCD (0-7): loop time in microseconds and the shader clock during the loop (shader cycles / wall time):\n")
     for r in rows:
@@ -326,7 +363,7 @@ def run_vendor(lib, out):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", default="mfma,lds,stamps,data")
+    ap.add_argument("--what", default="mfma,lds,valu,stamps,data,vendor")
     ap.add_argument("--json", default=None)
     args = ap.parse_args()
     import paper_2301_11913_amd as sw
@@ -335,7 +372,8 @@ def main():
     out = {}
     print("# Micro-benchmarks behind the GEMM roofline (MI355X; nominal %.1f GHz, 256 compute units)\n" % NOMINAL_GHZ)
     for w in args.what.split(","):
-        {"mfma": run_mfma, "lds": run_lds, "stamps": run_stamps, "data": run_data, "vendor": run_vendor}[w](lib, out)
+        {"mfma": run_mfma, "lds": run_lds, "valu": run_valu, "stamps": run_stamps, "data": run_data,
+         "vendor": run_vendor}[w](lib, out)
     if args.json:
         with open(args.json, "w") as f:
             json.dump(out, f, indent=1)
