@@ -15,6 +15,12 @@
 //                                          banks, so 32-byte pairs are XOR-ed with 2*(k-row & 3).
 //
 // One workgroup owns one output tile and walks K in order: deterministic.
+//
+// Three kernels share this file: gemm_bf16_dma_kernel (128 x 128 tiles, v_mfma_f32_32x32x16_bf16),
+// gemm_bf16_k32_kernel (256 x 256 and 256 x 128 tiles on eight wavefronts, v_mfma_f32_16x16x32_bf16: the dgrad and
+// wgrad layouts, the rotary and GeGLU epilogues) and gemm_bf16_w4_kernel (256 x 256 tiles on four wavefronts: the
+// forward layout with the store / bias / residual / int8-encoding / GeLU epilogues).  All accumulate a tile in the
+// same order, so which one runs a product does not change its bits.
 #include <algorithm>
 #include <type_traits>
 #include <utility>
