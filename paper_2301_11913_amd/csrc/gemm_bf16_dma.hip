@@ -19,8 +19,9 @@
 // Three kernels share this file: gemm_bf16_dma_kernel (128 x 128 tiles, v_mfma_f32_32x32x16_bf16),
 // gemm_bf16_k32_kernel (256 x 256 and 256 x 128 tiles on eight wavefronts, v_mfma_f32_16x16x32_bf16: the dgrad and
 // wgrad layouts, the rotary and GeGLU epilogues) and gemm_bf16_w4_kernel (256 x 256 tiles on four wavefronts: the
-// forward layout with the store / bias / residual / int8-encoding / GeLU epilogues).  All accumulate a tile in the
-// same order, so which one runs a product does not change its bits.
+// forward layout with the store / bias / residual / int8-encoding / GeLU epilogues).  The two 16 x 16 x 32 kernels
+// accumulate a tile in the same order and give the same bits; the 32 x 32 x 16 kernel agrees with them to fp32
+// rounding of the sums.
 #include <algorithm>
 #include <type_traits>
 #include <utility>
